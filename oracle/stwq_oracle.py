@@ -1,0 +1,294 @@
+"""CPU oracle for the STWQ + GPS quantized linear layer (PTQ4ARVG, arXiv 2601.21238).
+
+TEST INFRASTRUCTURE ONLY.  This file defines what "correct" means for the HIP
+library; it is imported by the tests, by the smoke check and by the benchmark's
+CPU-baseline leg, never by the product path.  It shares no code with the HIP
+sources and does not import the package.
+
+Everything is plain numpy, one step per function, in the order and notation of
+the paper:
+
+* Eq. 1 (Section 3, "Quantization"): uniform asymmetric quantizer
+  ``xbar = clamp(round(x / delta) + z, 0, 2^b - 1)``, ``delta = R / (2^b - 1)``,
+  ``z = round(-x_down / delta)``.
+* Eq. 2 (Section 3, "Equivalent Scaling"): ``Y = (X / s)(s * W)``.
+* Section 4.1 Step 4 and the appendix "Algorithm of GPS": the closed-form scale.
+* Section 4.2: one static ``(delta_t, z_t)`` per token position.
+* Appendix A.1: dequantization ``xhat = delta * (xbar - z)``.
+
+Precision.  The paper fixes no arithmetic for Eq. 1.  Integer codes are decided
+in IEEE fp32 by this exact sequence (each numpy ufunc rounds once, nothing is
+contracted): ``v = (x * inv_s[c]) * inv_delta[t]``; ``r = rint(v)`` (ties to
+even); ``code = clip(r + float(z_t), 0, 2^b - 1)``.  The reciprocals are made
+once with an IEEE fp32 divide.  Integer sums are exact.  The dequantized output
+and the GPS sums are fp64.
+
+Layouts.  X is [rows, K] with row r at token position ``r mod L``; W is
+[N, K] (out x in), i.e. the paper's ``W_{i,j}`` is ``W[j, i]`` here.
+
+Stored 8-bit activation codes are ``code - 128`` (the codes of Eq. 1 are
+unsigned; an int8 container is signed), and the zero point used with stored
+codes is ``z - 128``; ``code - z`` is unchanged.  6-bit codes 0..63 are stored
+as they are.
+
+Parity pins (tests/test_oracle_*.py): hand-made dyadic quantizer cases, the
+Delta/2 error bound, the folding identity, the n=2, m=1 closed form of Step 4
+and the stationarity of its gain function, brute-force integer matmul,
+Freivalds' check, and the dequantized-operand product in fp64.
+Percentile calibration is not implemented (the paper prints no percentile):
+min-max is used, and that choice is "parity unpinned" against the paper's
+accuracy tables, which need the pretrained models.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+F32 = np.float32
+
+
+def qmax_act(bits: int) -> int:
+    return (1 << bits) - 1
+
+
+def qmax_w(bits: int) -> int:
+    return (1 << (bits - 1)) - 1
+
+
+def store_offset(bits: int) -> int:
+    """Offset subtracted from an Eq. 1 code before it is stored in int8."""
+    return 128 if bits == 8 else 0
+
+
+# --------------------------------------------------------------------------- statistics
+
+def channel_stats(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Per input channel min, max and absmax of the raw activations over all rows
+    (the range step of the GPS algorithm)."""
+    x = np.asarray(x, dtype=F32)
+    return x.min(axis=0), x.max(axis=0), np.abs(x).max(axis=0)
+
+
+def position_stats(x: np.ndarray, inv_s: Optional[np.ndarray], L: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Per token position min and max of ``x * inv_s`` over all samples and channels
+    (Section 4.2: parameters are set offline per position; min-max calibration of Eq. 1)."""
+    x = np.asarray(x, dtype=F32)
+    rows, C = x.shape
+    assert rows % L == 0
+    xs = x if inv_s is None else x * np.asarray(inv_s, dtype=F32)[None, :]
+    xs = xs.reshape(rows // L, L, C)
+    return xs.min(axis=(0, 2)), xs.max(axis=(0, 2))
+
+
+def act_params(pos_min: np.ndarray, pos_max: np.ndarray, bits: int):
+    """Eq. 1's ``delta`` and ``z`` for every position, plus the reciprocal of delta.
+
+    The range is widened to contain 0 and z is clamped to the code range, so that
+    x = 0 is represented exactly."""
+    lo = np.minimum(np.asarray(pos_min, dtype=F32), F32(0))
+    hi = np.maximum(np.asarray(pos_max, dtype=F32), F32(0))
+    rng = np.maximum(hi - lo, F32(1e-8))
+    delta = (rng / F32(qmax_act(bits))).astype(F32)
+    inv_delta = (F32(1.0) / delta).astype(F32)
+    z = np.clip(np.rint((-lo) * inv_delta), 0, qmax_act(bits)).astype(np.int32)
+    return delta, inv_delta, z
+
+
+# --------------------------------------------------------------------------- Eq. 2 and weights
+
+def fold_weights(w: np.ndarray, s: Optional[np.ndarray]) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 2: ``W' = s * W`` (scale input channel k of every output row) and ``1 / s``."""
+    w = np.asarray(w, dtype=F32)
+    if s is None:
+        return w.copy(), np.ones(w.shape[1], dtype=F32)
+    s = np.asarray(s, dtype=F32)
+    return (w * s[None, :]).astype(F32), (F32(1.0) / s).astype(F32)
+
+
+def quantize_weights(w_folded: np.ndarray, bits: int):
+    """Symmetric per-output-channel weight quantizer: ``delta_w[o] = absmax_k / q_w``,
+    codes ``clip(rint(W' / delta_w))`` in [-2^(b-1), 2^(b-1) - 1], and their row sums."""
+    w = np.asarray(w_folded, dtype=F32)
+    qw = qmax_w(bits)
+    amax = np.abs(w).max(axis=1)
+    dw = np.where(amax > 0, amax / F32(qw), F32(1.0)).astype(F32)
+    inv = (F32(1.0) / dw).astype(F32)
+    codes = np.clip(np.rint(w * inv[:, None]), -(qw + 1), qw).astype(np.int8)
+    wsum = codes.astype(np.int64).sum(axis=1)
+    assert np.abs(wsum).max(initial=0) < 2**31
+    return codes, dw, wsum.astype(np.int32)
+
+
+# --------------------------------------------------------------------------- Eq. 1 on activations
+
+def quantize_act_codes(x: np.ndarray, inv_s: Optional[np.ndarray], inv_delta: np.ndarray,
+                       z: np.ndarray, L: int, bits: int) -> np.ndarray:
+    """Eq. 1 codes in 0..2^b-1 with the static parameters of each row's position."""
+    x = np.asarray(x, dtype=F32)
+    t = np.arange(x.shape[0]) % L
+    v = x if inv_s is None else x * np.asarray(inv_s, dtype=F32)[None, :]
+    v = v * np.asarray(inv_delta, dtype=F32)[t][:, None]
+    r = np.rint(v)
+    c = np.clip(r + np.asarray(z, dtype=np.int32)[t][:, None].astype(F32), F32(0), F32(qmax_act(bits)))
+    return c.astype(np.int32)
+
+
+def quantize_act(x, inv_s, inv_delta, z, L: int, bits: int) -> np.ndarray:
+    """Stored int8 codes: Eq. 1 code minus ``store_offset(bits)``."""
+    return (quantize_act_codes(x, inv_s, inv_delta, z, L, bits) - store_offset(bits)).astype(np.int8)
+
+
+# --------------------------------------------------------------------------- integer product and dequantization
+
+def gemm_i32(q: np.ndarray, wq: np.ndarray) -> np.ndarray:
+    """``acc[m, o] = sum_k q[m, k] * wq[o, k]`` exactly.
+
+    Every product is an integer below 2^14 in magnitude and every partial sum is
+    below 2^31, far inside fp64's 2^53 exact-integer range, so an fp64 matmul in any
+    summation order returns the exact integer."""
+    acc = q.astype(np.float64) @ wq.astype(np.float64).T
+    assert np.abs(acc).max(initial=0) < 2**31
+    return acc.astype(np.int64).astype(np.int32)
+
+
+def epilogue(acc: np.ndarray, z: np.ndarray, wsum: np.ndarray, delta: np.ndarray, dw: np.ndarray,
+             bias: Optional[np.ndarray], L: int, bits: int) -> np.ndarray:
+    """Appendix A.1 dequantization of the product, unrounded fp64:
+
+    ``sum_k delta_t (code - z_t) * delta_w Wq = delta_t delta_w (acc - (z_t - off) wsum[o])``."""
+    t = np.arange(acc.shape[0]) % L
+    zs = (np.asarray(z, dtype=np.int64) - store_offset(bits))[t]
+    corr = acc.astype(np.int64) - zs[:, None] * wsum.astype(np.int64)[None, :]
+    assert np.abs(corr).max(initial=0) < 2**31
+    y = corr.astype(np.float64) * (delta.astype(np.float64)[t][:, None] * dw.astype(np.float64)[None, :])
+    if bias is not None:
+        y = y + bias.astype(np.float64)[None, :]
+    return y
+
+
+def to_bf16_bits(y: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even bf16 bit patterns of finite values (informational only)."""
+    u = np.asarray(y, dtype=F32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
+    return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(F32).astype(np.float64)
+
+
+# --------------------------------------------------------------------------- GPS (Section 4.1, appendix algorithm)
+
+def fake_quant_per_tensor(x: np.ndarray, bits: int, lo: float, hi: float) -> np.ndarray:
+    """Eq. 1 followed by dequantization with one (delta, z) for the whole tensor, fp64."""
+    lo = min(float(lo), 0.0)
+    hi = max(float(hi), 0.0)
+    delta = max(hi - lo, 1e-30) / qmax_act(bits)
+    z = np.rint(-lo / delta)
+    code = np.clip(np.rint(x.astype(np.float64) / delta) + z, 0, qmax_act(bits))
+    return delta * (code - z)
+
+
+def fake_quant_weights(w: np.ndarray, bits: int) -> np.ndarray:
+    """Per-output-channel symmetric quantize-dequantize of the unscaled weights, fp64."""
+    w = w.astype(np.float64)
+    qw = qmax_w(bits)
+    amax = np.abs(w).max(axis=1, keepdims=True)
+    dw = np.where(amax > 0, amax / qw, 1.0)
+    return dw * np.clip(np.rint(w / dw), -(qw + 1), qw)
+
+
+def gps_error_sums(x: np.ndarray, w: np.ndarray, a_bits: int, w_bits: int,
+                   rows_per_chunk: int = 16384) -> Dict[str, np.ndarray]:
+    """Step 1 and 2 of the algorithm: quantization errors and ranges, reduced to the
+    per-input-channel sums the closed form needs.
+
+    ``sum_j |dW_ij x_i|`` summed over rows factorises into ``(sum_j |dW_ij|)(sum_r |x_ri|)``,
+    likewise for ``|W_ij dx_i|``."""
+    x = np.asarray(x, dtype=F32)
+    w = np.asarray(w, dtype=F32)
+    ch_min, ch_max, ch_absmax = channel_stats(x)
+    lo, hi = float(ch_min.min()), float(ch_max.max())
+    sum_abs_x = np.zeros(x.shape[1])
+    sum_abs_dx = np.zeros(x.shape[1])
+    for r0 in range(0, x.shape[0], rows_per_chunk):
+        xc = x[r0:r0 + rows_per_chunk]
+        dx = xc.astype(np.float64) - fake_quant_per_tensor(xc, a_bits, lo, hi)
+        sum_abs_x += np.abs(xc.astype(np.float64)).sum(axis=0)
+        sum_abs_dx += np.abs(dx).sum(axis=0)
+    dw_err = w.astype(np.float64) - fake_quant_weights(w, w_bits)
+    return {
+        "ch_min": ch_min, "ch_max": ch_max, "ch_absmax": ch_absmax,
+        "sum_abs_x": sum_abs_x, "sum_abs_dx": sum_abs_dx,
+        "sum_abs_w": np.abs(w.astype(np.float64)).sum(axis=0),      # over outputs j, per input i
+        "sum_abs_dw": np.abs(dw_err).sum(axis=0),
+        "w_min": w.min(axis=0), "w_max": w.max(axis=0), "w_absmax": np.abs(w).max(axis=0),
+    }
+
+
+def gps_anchor(r_x_k: float, r_w_k: float) -> float:
+    """Step 3: ``s_k = sqrt(R_x^k / R_w^k)`` so that the two ranges meet after scaling."""
+    return float(np.sqrt(r_x_k / r_w_k))
+
+
+def gps_closed_form(s_k: float, sum_dw_x, sum_w_dx):
+    """Step 4 (the extension of the single-output optimum to all outputs):
+    ``s_i = s_k sqrt(sum |dW_ij x_i|) / sqrt(sum |W_ij dx_i|)``."""
+    return s_k * np.sqrt(sum_dw_x) / np.sqrt(sum_w_dx)
+
+
+def gps_scale(x: np.ndarray, w: np.ndarray, a_bits: int, w_bits: int,
+              range_mode: str = "absmax") -> np.ndarray:
+    """The GPS algorithm end to end: fp32 scale per input channel.
+
+    ``range_mode`` chooses ``R = max - min`` ("minmax") or ``R = 2 absmax`` ("absmax") for
+    both the activation channel and input-channel row k of the weights."""
+    e = gps_error_sums(x, w, a_bits, w_bits)
+    if range_mode == "minmax":
+        r_x = e["ch_max"].astype(np.float64) - e["ch_min"].astype(np.float64)
+        r_w = e["w_max"].astype(np.float64) - e["w_min"].astype(np.float64)
+    elif range_mode == "absmax":
+        r_x = 2.0 * e["ch_absmax"].astype(np.float64)
+        r_w = 2.0 * e["w_absmax"].astype(np.float64)
+    else:
+        raise ValueError(range_mode)
+    k = int(np.argmax(r_x))                       # ties: lowest index
+    s_k = gps_anchor(r_x[k], r_w[k]) if r_x[k] > 0 and r_w[k] > 0 else 1.0
+    num = e["sum_abs_dw"] * e["sum_abs_x"]
+    den = e["sum_abs_w"] * e["sum_abs_dx"]
+    ok = (num > 0) & (den > 0)
+    s = np.ones_like(num)
+    s[ok] = gps_closed_form(s_k, num[ok], den[ok])
+    s[k] = s_k
+    return np.clip(s, 1e-5, 1e5).astype(F32)
+
+
+# --------------------------------------------------------------------------- whole layer
+
+def calibrate_layer(x_calib: np.ndarray, w: np.ndarray, bias: Optional[np.ndarray], L: int,
+                    a_bits: int, w_bits: int, use_gps: bool, s: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Offline stage: scale, fold, weight codes, static per-position parameters."""
+    if s is None and use_gps:
+        s = gps_scale(x_calib, w, a_bits, w_bits)
+    w_folded, inv_s = fold_weights(w, s)
+    wq, dw, wsum = quantize_weights(w_folded, w_bits)
+    pos_min, pos_max = position_stats(x_calib, None if s is None else inv_s, L)
+    delta, inv_delta, z = act_params(pos_min, pos_max, a_bits)
+    return {"s": s, "inv_s": None if s is None else inv_s, "wq": wq, "dw": dw, "wsum": wsum,
+            "pos_min": pos_min, "pos_max": pos_max, "delta": delta, "inv_delta": inv_delta, "z": z,
+            "bias": bias, "L": L, "a_bits": a_bits, "w_bits": w_bits}
+
+
+def forward(pack: Dict[str, np.ndarray], x: np.ndarray, t0: Optional[int] = None):
+    """Online stage.  With ``t0`` every row uses position ``t0`` (decode step).
+    Returns stored int8 codes, int32 accumulators and the unrounded fp64 output."""
+    if t0 is None:
+        L, delta, inv_delta, z = pack["L"], pack["delta"], pack["inv_delta"], pack["z"]
+    else:
+        L = 1
+        delta, inv_delta, z = (pack[k][t0:t0 + 1] for k in ("delta", "inv_delta", "z"))
+    q = quantize_act(x, pack["inv_s"], inv_delta, z, L, pack["a_bits"])
+    acc = gemm_i32(q, pack["wq"])
+    y = epilogue(acc, z, pack["wsum"], delta, pack["dw"], pack["bias"], L, pack["a_bits"])
+    return q, acc, y

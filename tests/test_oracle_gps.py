@@ -1,0 +1,118 @@
+"""Pins for the oracle's GPS scale (Section 4.1 Step 4 and the appendix algorithm)."""
+import json
+import os
+
+import numpy as np
+
+from oracle import stwq_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+F32 = np.float32
+
+
+def _gold():
+    with open(os.path.join(GOLD, "gps_two_channel.json")) as f:
+        return json.load(f)
+
+
+def test_two_channel_hand_case():
+    g = _gold()
+    x = np.array(g["x"], F32)
+    w = np.array(g["w_out_in"], F32)
+    h = g["hand"]
+    lo, hi = x.min(), x.max()
+    assert np.array_equal(O.fake_quant_per_tensor(x, g["a_bits"], lo, hi), np.array(h["x_dequant"]))
+    assert np.array_equal(O.fake_quant_weights(w, g["w_bits"]), np.array(h["w_dequant"]))
+    e = O.gps_error_sums(x, w, g["a_bits"], g["w_bits"])
+    for key in ("sum_abs_x", "sum_abs_dx", "sum_abs_w", "sum_abs_dw"):
+        assert np.array_equal(e[key], np.array(h[key])), key
+    s = O.gps_scale(x, w, g["a_bits"], g["w_bits"], "absmax")
+    assert s.dtype == F32 and np.allclose(s, h["s_absmax"], rtol=1e-6)
+    s = O.gps_scale(x, w, g["a_bits"], g["w_bits"], "minmax")
+    assert np.allclose(s, h["s_minmax"], rtol=1e-6)
+
+
+def test_factorised_sums_equal_the_double_sum():
+    # sum over rows and outputs of |dW_ij x_ri| written out as loops
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((7, 3)).astype(F32)
+    w = rng.standard_normal((4, 3)).astype(F32)
+    e = O.gps_error_sums(x, w, 4, 4)
+    xq = O.fake_quant_per_tensor(x, 4, x.min(), x.max())
+    wq = O.fake_quant_weights(w, 4)
+    for i in range(3):
+        num = sum(abs((float(w[j, i]) - wq[j, i]) * float(x[r, i])) for r in range(7) for j in range(4))
+        den = sum(abs(float(w[j, i]) * (float(x[r, i]) - xq[r, i])) for r in range(7) for j in range(4))
+        assert np.isclose(num, e["sum_abs_dw"][i] * e["sum_abs_x"][i], rtol=1e-12)
+        assert np.isclose(den, e["sum_abs_w"][i] * e["sum_abs_dx"][i], rtol=1e-12)
+
+
+def test_single_output_closed_form_and_stationarity():
+    so = _gold()["single_output"]
+    s1, a, b = so["s1"], so["abs_dW_x"], so["abs_W_dx"]     # a = |dW x|, b = |W dx|
+    s2 = O.gps_closed_form(s1, a, b)
+    assert np.isclose(s2, so["s2"], rtol=1e-12)
+
+    def gain(t):   # Step 4's g(s_2) for one output, constants dropped
+        return -0.5 * (t * t / (s1 * s1)) * b * b - 0.5 * (s1 * s1 / (t * t)) * a * a
+
+    def dgain(t):  # its printed derivative
+        return -(t / s1 ** 2) * b * b + (s1 ** 2 / t ** 3) * a * a
+
+    assert abs(dgain(s2)) < 1e-15
+    grid = np.linspace(0.2, 20, 20001)
+    assert abs(grid[np.argmax(gain(grid))] - s2) < 2e-3
+    assert gain(s2) > gain(s2 * 1.05) and gain(s2) > gain(s2 / 1.05)
+
+
+def test_anchor_equalises_ranges():
+    # Step 4: s_1 = sqrt(R_x / R_W) makes R_x / s_1 == R_W * s_1
+    for rx, rw in [(900.0, 0.07), (3.0, 5.0), (1.0, 1.0)]:
+        s = O.gps_anchor(rx, rw)
+        assert np.isclose(rx / s, rw * s, rtol=1e-12)
+
+
+def test_outlier_channels_get_larger_scale_and_edge_cases():
+    rng = np.random.default_rng(1)
+    n, C, N = 4096, 32, 24
+    x = rng.standard_normal((n, C)).astype(F32)
+    x[:, [3, 17]] *= 50
+    w = (rng.standard_normal((N, C)) * 0.02).astype(F32)
+    s = O.gps_scale(x, w, 8, 8)
+    normal = np.delete(s, [3, 17])
+    assert s[3] > normal.max() and s[17] > normal.max()        # Remark 1 (sanity, not a paper value)
+    assert np.all(s >= F32(1e-5)) and np.all(s <= F32(1e5))
+    # dead input channel (all zero) and zero weight column: scale falls back to 1
+    x[:, 5] = 0
+    w[:, 9] = 0
+    s = O.gps_scale(x, w, 8, 8)
+    assert s[5] == 1 and s[9] == 1
+    # argmax ties resolve to the lowest index
+    x2 = np.zeros((4, 3), F32)
+    x2[0] = [2, 2, 1]
+    x2[1] = [-2, -2, -1]
+    w2 = np.array([[1, 0.5, 1], [0.5, 2, 1]], F32)
+    s = O.gps_scale(x2, w2, 8, 8)
+    assert np.isclose(s[0], np.sqrt(4 / 2))                    # anchor is channel 0, R_w^0 = 2*1
+
+
+def test_gps_scaling_reduces_end_to_end_error_on_outlier_data():
+    rng = np.random.default_rng(4)
+    L, C, N, n = 8, 64, 48, 64
+    std = rng.uniform(0.5, 4, L)
+    def draw(m):
+        x = rng.standard_normal((m, L, C)) * std[None, :, None]
+        x[:, :, [1, 40]] *= 50
+        return x.reshape(m * L, C).astype(F32)
+    xc = draw(n)
+    w = (rng.standard_normal((N, C)) * 0.02).astype(F32)
+    b = (rng.standard_normal(N) * 0.01).astype(F32)
+    # measured on the calibration draw itself, so rounding (what scaling acts on) and not
+    # clipping of unseen extremes (which min-max calibration cannot prevent) decides the error
+    ref = xc.astype(np.float64) @ w.astype(np.float64).T + b
+    errs = {}
+    for gps in (False, True):
+        pack = O.calibrate_layer(xc, w, b, L, 8, 8, gps)
+        _, _, y = O.forward(pack, xc)
+        errs[gps] = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+    assert errs[True] < 0.5 * errs[False] and errs[True] < 0.02

@@ -1,0 +1,152 @@
+"""Pins for the oracle's Eq. 1 quantizer, Eq. 2 folding and the weight quantizer."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import stwq_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+F32 = np.float32
+
+
+def _cases():
+    with open(os.path.join(GOLD, "quantizer_dyadic.json")) as f:
+        return json.load(f)["cases"]
+
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: f"b{c['bits']}")
+def test_dyadic_hand_cases(case):
+    b = case["bits"]
+    delta, inv_delta, z = O.act_params(np.array([case["pos_min"]], F32), np.array([case["pos_max"]], F32), b)
+    assert delta[0] == F32(case["delta"]) and inv_delta[0] == F32(case["inv_delta"]) and z[0] == case["z"]
+    x = np.array(case["x"], F32)[:, None]                      # one channel, rows all at position 0
+    codes = O.quantize_act_codes(x, None, inv_delta, z, 1, b)[:, 0]
+    assert codes.tolist() == case["codes"]
+    stored = O.quantize_act(x, None, inv_delta, z, 1, b)[:, 0]
+    assert stored.dtype == np.int8
+    assert (stored.astype(np.int32) + O.store_offset(b)).tolist() == case["codes"]
+
+
+def test_inv_s_is_applied_before_inv_delta():
+    # x * inv_s lands on a tie only if the channel scale is applied: 5 * (1/2) = 2.5 steps -> 2
+    x = np.array([[5.0, 5.0]], F32)
+    inv_s = np.array([0.5, 1.0], F32)
+    codes = O.quantize_act_codes(x, inv_s, np.array([1.0], F32), np.array([10], np.int32), 1, 8)
+    assert codes.tolist() == [[12, 15]]
+
+
+def test_position_indexing_is_row_mod_L():
+    L = 3
+    inv_delta = np.array([1.0, 2.0, 4.0], F32)
+    z = np.array([1, 2, 3], np.int32)
+    x = np.ones((7, 1), F32)
+    codes = O.quantize_act_codes(x, None, inv_delta, z, L, 8)[:, 0]
+    assert codes.tolist() == [2, 4, 7, 2, 4, 7, 2]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+def test_error_bound_monotone_zero_exact(bits):
+    rng = np.random.default_rng(7)
+    L, C, n = 5, 64, 40
+    x = (rng.standard_normal((n * L, C)) * rng.uniform(0.5, 4, (1, C))).astype(F32)
+    inv_s = (1.0 / rng.uniform(0.5, 8, C)).astype(F32)
+    pmin, pmax = O.position_stats(x, inv_s, L)
+    delta, inv_delta, z = O.act_params(pmin, pmax, bits)
+    codes = O.quantize_act_codes(x, inv_s, inv_delta, z, L, bits)
+    assert codes.min() >= 0 and codes.max() <= O.qmax_act(bits)
+    t = np.arange(n * L) % L
+    xs = (x * inv_s[None, :]).astype(np.float64)
+    deq = delta.astype(np.float64)[t][:, None] * (codes - z[t][:, None])
+    # calibration data lie inside [lo, hi]: the reconstruction error is at most half a step
+    bound = 0.5 * delta.astype(np.float64)[t][:, None] * (1 + 2.0 ** -18)
+    assert np.all(np.abs(xs - deq) <= bound)
+    # the extreme of every position reaches the end of the code range it sits on
+    for tt in range(L):
+        assert codes[t == tt].max() == O.qmax_act(bits) or codes[t == tt].min() == 0
+    # zero maps to the zero point and dequantizes to exactly zero
+    zc = O.quantize_act_codes(np.zeros((L, C), F32), inv_s, inv_delta, z, L, bits)
+    assert np.all(zc == z[:, None])
+    # monotone in x (one position, one channel)
+    xs1 = np.sort(rng.standard_normal(2000).astype(F32) * 3)[:, None]
+    c1 = O.quantize_act_codes(xs1, None, inv_delta[:1], z[:1], 1, bits)[:, 0]
+    assert np.all(np.diff(c1) >= 0)
+
+
+def test_scaling_inputs_and_ranges_by_power_of_two_keeps_codes():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((12, 16)).astype(F32)
+    pmin, pmax = O.position_stats(x, None, 4)
+    d1, i1, z1 = O.act_params(pmin, pmax, 8)
+    d2, i2, z2 = O.act_params(pmin * F32(8), pmax * F32(8), 8)
+    assert np.all(z1 == z2)
+    c1 = O.quantize_act_codes(x, None, i1, z1, 4, 8)
+    c2 = O.quantize_act_codes(x * F32(8), None, i2, z2, 4, 8)
+    assert np.array_equal(c1, c2)
+
+
+def test_range_is_widened_to_contain_zero_and_degenerate_range():
+    d, i, z = O.act_params(np.array([1.0, 0.0], F32), np.array([3.0, 0.0], F32), 8)
+    assert z[0] == 0 and d[0] == F32(3.0) / F32(255)
+    assert d[1] > 0 and np.isfinite(i[1]) and z[1] == 0
+    d, i, z = O.act_params(np.array([-3.0], F32), np.array([-1.0], F32), 8)
+    assert z[0] == 255
+
+
+def test_position_stats_against_loops():
+    rng = np.random.default_rng(11)
+    L, C, n = 4, 6, 5
+    x = rng.standard_normal((n * L, C)).astype(F32)
+    inv_s = rng.uniform(0.1, 2, C).astype(F32)
+    pmin, pmax = O.position_stats(x, inv_s, L)
+    for t in range(L):
+        vals = [F32(x[r, c]) * F32(inv_s[c]) for r in range(n * L) if r % L == t for c in range(C)]
+        assert pmin[t] == min(vals) and pmax[t] == max(vals)
+    cmin, cmax, camax = O.channel_stats(x)
+    for c in range(C):
+        assert cmin[c] == x[:, c].min() and cmax[c] == x[:, c].max()
+        assert camax[c] == max(abs(float(v)) for v in x[:, c])
+
+
+def test_folding_identity():
+    # Eq. 2: (X / s)(s * W) = X W
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((9, 33)).astype(F32)
+    w = rng.standard_normal((17, 33)).astype(F32)
+    s = rng.uniform(0.05, 20, 33).astype(F32)
+    wf, inv_s = O.fold_weights(w, s)
+    assert np.array_equal(wf, w * s[None, :])
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    got = (x * inv_s[None, :]).astype(np.float64) @ wf.astype(np.float64).T
+    assert np.allclose(got, ref, rtol=0, atol=1e-5 * np.abs(ref).max())
+    # exact for powers of two
+    s2 = (2.0 ** rng.integers(-3, 4, 33)).astype(F32)
+    wf, inv_s = O.fold_weights(w, s2)
+    got = (x * inv_s[None, :]).astype(np.float64) @ wf.astype(np.float64).T
+    assert np.array_equal(got, ref)
+    wf, inv_s = O.fold_weights(w, None)
+    assert np.array_equal(wf, w) and np.all(inv_s == 1)
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+def test_weight_quantizer(bits):
+    rng = np.random.default_rng(2)
+    w = (rng.standard_normal((20, 48)) * 0.02).astype(F32)
+    w[3] = 0                                           # dead row
+    wq, dw, wsum = O.quantize_weights(w, bits)
+    q = O.qmax_w(bits)
+    assert wq.dtype == np.int8 and wq.min() >= -q and wq.max() <= q
+    assert np.all(np.abs(w.astype(np.float64) - dw.astype(np.float64)[:, None] * wq) <= 0.5 * dw[:, None] * (1 + 1e-6))
+    for o in range(20):
+        if o == 3:
+            assert dw[o] == 1 and not wq[o].any()
+            continue
+        k = int(np.argmax(np.abs(w[o])))
+        assert abs(int(wq[o, k])) == q
+        assert dw[o] == np.abs(w[o]).max() / F32(q)
+        assert wsum[o] == sum(int(v) for v in wq[o])
+    # dyadic row: absmax 127/64 -> delta 1/64, ties to even
+    row = np.array([[127 / 64, 2.5 / 64, 3.5 / 64, -0.5 / 64, -127 / 64]], F32)
+    wq, dw, wsum = O.quantize_weights(row, 8)
+    assert dw[0] == F32(1 / 64) and wq[0].tolist() == [127, 2, 4, 0, -127] and wsum[0] == 6

@@ -1,0 +1,198 @@
+"""Seeded synthetic inputs shaped like the ARVG linear layers the paper quantizes.
+
+This module only draws random tensors (weights, biases, calibration and test
+activations).  It contains none of the method's arithmetic (no quantizer, no
+scale solve, no matmul): the CPU oracle and the HIP library each receive the
+same bytes from here and compute everything else on their own.
+
+The tensors stand in for activations of the pretrained VAR / RAR / PAR / MAR
+decoders (Section 5, "Models and Metrics"), which need ImageNet-trained weights
+that are not available offline.  The recipe reproduces the three structural
+properties the method relies on:
+
+* a few input channels with outliers (what Gain-Projected Scaling, Section 4.1,
+  is for): ``n_outliers`` channels multiplied by ``gain``;
+* a scale that varies along the token sequence but is the same for every
+  sample at a given position (the two properties behind Static Token-Wise
+  Quantization, Section 4.2): one ``pos_std[t] ~ U[0.5, 4]`` per position,
+  shared by calibration and test draws;
+* fc2 inputs that are GELU outputs (heavy positive tail, bounded below).
+
+Seeds follow ``21238 * 10**4 + config * 10**3 + layer * 10 + role`` with
+role 0 = weight, 1 = bias, 2 = outlier set, 3 = pos_std, 4 = calibration
+activations, 5 = test activations, 6 = decode position.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, Iterator, List, Tuple
+
+import numpy as np
+from scipy.special import erf
+
+ROLE_W, ROLE_BIAS, ROLE_OUTLIERS, ROLE_POS_STD, ROLE_CALIB, ROLE_TEST, ROLE_POS = range(7)
+
+
+@dataclass(frozen=True)
+class LinearSpec:
+    """One linear layer of one configuration."""
+    config: int            # 1..5, index into the list of configurations
+    layer: int             # seed slot (block index * 4 + position in block)
+    name: str              # qkv / proj / fc1 / fc2
+    K: int                 # input channels  (C_in)
+    N: int                 # output channels (C_out)
+    L: int                 # token positions with their own static parameters
+    batch: int             # samples per forward (CFG doubling included)
+    n_calib: int           # calibration samples
+    n_outliers: int
+    gain: float
+    gelu_input: bool       # fc2: activations are GELU outputs
+    gps: bool              # scale solved by GPS (qkv, fc1) or ones (proj, fc2)
+    a_bits: int = 8
+    w_bits: int = 8
+    decode: bool = False   # all rows share one token position
+
+    @property
+    def M(self) -> int:
+        return self.batch if self.decode else self.batch * self.L
+
+    def seed(self, role: int) -> int:
+        return 21238 * 10**4 + self.config * 10**3 + self.layer * 10 + role
+
+
+def _block(config: int, block: int, hidden: int, L: int, batch: int, n_calib: int,
+           n_outliers: int, gain: float, bits: int, decode: bool = False,
+           names: Tuple[str, ...] = ("qkv", "proj", "fc1", "fc2")) -> List[LinearSpec]:
+    shapes = {
+        "qkv": (hidden, 3 * hidden, False, True),
+        "proj": (hidden, hidden, False, False),
+        "fc1": (hidden, 4 * hidden, False, True),
+        "fc2": (4 * hidden, hidden, True, False),
+    }
+    order = ("qkv", "proj", "fc1", "fc2")
+    out = []
+    for nm in names:
+        K, N, gelu, gps = shapes[nm]
+        out.append(LinearSpec(config, block * 4 + order.index(nm), nm, K, N, L, batch, n_calib,
+                              n_outliers, gain, gelu, gps, bits, bits, decode))
+    return out
+
+
+VAR_PYRAMID = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+L_VAR = sum(p * p for p in VAR_PYRAMID)          # 680 token positions
+
+
+def config_linears(config: int, bits: int = 8, blocks: int | None = None) -> List[LinearSpec]:
+    """The linears of configuration 1..5 (``bits`` = 8 for W8A8, 6 for W6A6)."""
+    if config == 1:
+        return [LinearSpec(1, 0, "qkv", 1024, 1024, L_VAR, 1, 32, 8, 50.0, False, True, bits, bits)]
+    if config == 2:   # VAR-d16-shaped block, batch 16 x 2 (CFG)
+        return _block(2, 0, 1024, L_VAR, 32, 64, 8, 50.0, bits)
+    if config == 3:   # VAR-d30-shaped block at hidden 1920, batch 32 x 2
+        return _block(3, 0, 1920, L_VAR, 64, 64, 16, 100.0, bits)
+    if config == 4:   # RAR-XXL-shaped decode step, 24 layers, M = 64 x 2 rows at one position
+        n = 24 if blocks is None else blocks
+        out: List[LinearSpec] = []
+        for b in range(n):
+            out += _block(4, b, 1280, 256, 128, 8, 8, 50.0, bits, decode=True,
+                          names=("qkv", "fc1", "fc2"))
+        return out
+    if config == 5:   # 3B-class PAR/MAR-shaped prefill, 30 blocks, batch 8 x 2, 32 x 32 grid
+        n = 30 if blocks is None else blocks
+        out = []
+        for b in range(n):
+            out += _block(5, b, 3072, 1024, 16, 32, 16, 100.0, bits)
+        return out
+    raise ValueError(f"unknown config {config}")
+
+
+def shrink(spec: LinearSpec, **kw) -> LinearSpec:
+    """Same recipe at another size (used by the small parity cases)."""
+    return replace(spec, **kw)
+
+
+def _rng(spec: LinearSpec, role: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(spec.seed(role)))
+
+
+def make_weights(spec: LinearSpec) -> Tuple[np.ndarray, np.ndarray]:
+    """W [N, K] ~ N(0, 0.02^2) and bias [N] ~ N(0, 0.01^2), fp32, K contiguous."""
+    w = _rng(spec, ROLE_W).standard_normal((spec.N, spec.K), dtype=np.float32)
+    w *= np.float32(0.02)
+    b = _rng(spec, ROLE_BIAS).standard_normal(spec.N, dtype=np.float32)
+    b *= np.float32(0.01)
+    return w, b
+
+
+def make_outliers(spec: LinearSpec) -> np.ndarray:
+    idx = _rng(spec, ROLE_OUTLIERS).choice(spec.K, size=min(spec.n_outliers, spec.K), replace=False)
+    return np.sort(idx).astype(np.int64)
+
+
+def make_pos_std(spec: LinearSpec) -> np.ndarray:
+    return _rng(spec, ROLE_POS_STD).uniform(0.5, 4.0, size=spec.L).astype(np.float32)
+
+
+def decode_position(spec: LinearSpec) -> int:
+    """The one token position all rows of a decode step sit at."""
+    return int(_rng(spec, ROLE_POS).integers(0, spec.L))
+
+
+def _gelu_erf(x: np.ndarray) -> np.ndarray:
+    # input shaping only: fc2 sees the output of the FFN's GELU
+    return (x * (np.float32(0.5) * (np.float32(1.0) + erf(x * np.float32(0.7071067811865476))))).astype(np.float32)
+
+
+def _channel_gain(spec: LinearSpec) -> np.ndarray:
+    g = np.ones(spec.K, dtype=np.float32)
+    g[make_outliers(spec)] = np.float32(spec.gain)
+    return g
+
+
+def activation_chunks(spec: LinearSpec, n_samples: int, role: int,
+                      samples_per_chunk: int = 8) -> Iterator[np.ndarray]:
+    """Yield [s * L, K] fp32 chunks of ``n_samples`` full sequences, sample-major rows
+    (row r sits at position r mod L)."""
+    rng = _rng(spec, role)
+    std = make_pos_std(spec)[:, None]
+    gain = _channel_gain(spec)[None, :]
+    done = 0
+    while done < n_samples:
+        s = min(samples_per_chunk, n_samples - done)
+        x = rng.standard_normal((s, spec.L, spec.K), dtype=np.float32)
+        x *= std
+        x *= gain
+        x = x.reshape(s * spec.L, spec.K)
+        if spec.gelu_input:
+            x = _gelu_erf(x)
+        yield x
+        done += s
+
+
+def make_activations(spec: LinearSpec, n_samples: int, role: int) -> np.ndarray:
+    """[n_samples * L, K] fp32."""
+    return np.concatenate(list(activation_chunks(spec, n_samples, role)), axis=0)
+
+
+def make_calibration(spec: LinearSpec) -> np.ndarray:
+    return make_activations(spec, spec.n_calib, ROLE_CALIB)
+
+
+def make_test_input(spec: LinearSpec) -> np.ndarray:
+    """Prefill: [batch * L, K].  Decode: [batch, K], every row at ``decode_position``."""
+    if not spec.decode:
+        return make_activations(spec, spec.batch, ROLE_TEST)
+    t = decode_position(spec)
+    rng = _rng(spec, ROLE_TEST)
+    x = rng.standard_normal((spec.batch, spec.K), dtype=np.float32)
+    x *= make_pos_std(spec)[t]
+    x *= _channel_gain(spec)[None, :]
+    if spec.gelu_input:
+        x = _gelu_erf(x)
+    return x
+
+
+def describe(spec: LinearSpec) -> Dict[str, object]:
+    return {"config": spec.config, "layer": spec.layer, "name": spec.name, "M": spec.M,
+            "K": spec.K, "N": spec.N, "L": spec.L, "a_bits": spec.a_bits, "w_bits": spec.w_bits,
+            "decode": spec.decode}
