@@ -1,0 +1,129 @@
+/* stwq.h — C ABI of the MI355X (gfx950) library for the statically token-wise quantized
+ * (STWQ) linear layer with Gain-Projected-Scaling (GPS) channel scales folded into the weights
+ * (PTQ4ARVG, arXiv 2601.21238).
+ *
+ * Conventions
+ *  - Every pointer whose name ends in _dev is DEVICE memory owned by the caller (for example a
+ *    torch tensor's data_ptr()).  The library never allocates, frees or keeps any of them.
+ *    Pointers without _dev are HOST memory.
+ *  - stream is a hipStream_t passed as void* (NULL = the default stream).  Device entry points
+ *    enqueue their kernels on it and return without synchronising.
+ *  - Matrices are dense row-major: activations X[rows, K] (row r sits at token position r mod L),
+ *    weights W[N, K] (output channel x input channel, K contiguous).  The paper writes W as
+ *    n x m (in x out), so its W_{i,j} is W[j, i] here.
+ *  - Return value: STWQ_OK, or a negative code.  Arguments are checked before any HIP call, so
+ *    STWQ_EINVAL paths run without a GPU.  stwq_last_error() describes the last failure of the
+ *    calling thread.
+ *  - Bit widths: 8 or 6.  Activation codes follow Eq. 1 (Section 3) and lie in 0 .. 2^b - 1; an
+ *    8-bit code is STORED in int8 as code - 128 and used with zero point z - 128 (code - z is
+ *    unchanged); 6-bit codes 0..63 are stored as they are.  Weight codes are symmetric,
+ *    -(2^(b-1) - 1) .. 2^(b-1) - 1.
+ *  - fp32 arithmetic that decides an integer is fixed (each step rounds once, no fused
+ *    multiply-add): v = (x * inv_s[c]) * inv_delta[t]; r = round-half-even(v);
+ *    code = clamp(r + float(z_t), 0, 2^b - 1).
+ */
+#ifndef STWQ_H
+#define STWQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported symbols (the library is built with hidden default visibility). */
+#define STWQ_API __attribute__((visibility("default")))
+
+#define STWQ_OK            0
+#define STWQ_EINVAL       (-1)   /* null pointer, non-positive size, unsupported bit width, misalignment */
+#define STWQ_EUNSUPPORTED (-2)   /* valid request this build cannot serve */
+#define STWQ_EHIP         (-3)   /* a HIP runtime call failed; message holds hipGetErrorString */
+
+/* Description of the calling thread's last error (never NULL; "" if none). */
+STWQ_API const char* stwq_last_error(void);
+
+/* Library version string. */
+STWQ_API const char* stwq_version(void);
+
+/* Calibration statistics (the ranges Eq. 1 needs; the range step of the GPS algorithm in the
+ * appendix; Section 4.2: per-position parameters are set offline).
+ *   x_dev      [rows, C] fp32, rows a multiple of L, 16-byte aligned, C a multiple of 4.
+ *   inv_s_dev  [C] fp32 reciprocal GPS scale or NULL (= ones).  Position statistics are taken of
+ *              x * inv_s; channel statistics of the raw x.
+ *   pos_min_dev, pos_max_dev  [L] fp32, both or neither.  In/out: results are MERGED (min / max)
+ *              into what the buffers hold, so a calibration set can be streamed through several
+ *              calls.  Initialise with +inf / -inf.
+ *   ch_min_dev, ch_max_dev, ch_absmax_dev  [C] fp32, each may be NULL.  In/out as above
+ *              (initialise +inf / -inf / 0).
+ * At least one output must be given.  Results are exact and independent of scheduling. */
+STWQ_API int stwq_calibrate_stats(const float* x_dev, int64_t rows, int L, int C,
+                         const float* inv_s_dev,
+                         float* pos_min_dev, float* pos_max_dev,
+                         float* ch_min_dev, float* ch_max_dev, float* ch_absmax_dev,
+                         void* stream);
+
+/* HOST helper.  Eq. 1's delta_t and z_t from per-position min / max (min-max calibration), plus
+ * the reciprocal the quantize kernel multiplies by:
+ *   lo = min(pos_min, 0); hi = max(pos_max, 0); delta = max(hi - lo, 1e-8f) / (2^b - 1);
+ *   inv_delta = 1.0f / delta; z = clamp(round-half-even(-lo * inv_delta), 0, 2^b - 1).
+ * All arrays are host arrays of length L. */
+STWQ_API int stwq_finalize_act_params(const float* pos_min, const float* pos_max, int L, int a_bits,
+                             float* delta, float* inv_delta, int32_t* zp);
+
+/* Equivalent scaling folded into the weights (Eq. 2) and per-output-channel symmetric weight
+ * quantization:
+ *   W'[o,k] = s[k] * W[o,k];  dw[o] = max_k |W'[o,k]| / (2^(b-1) - 1)  (1.0 for an all-zero row);
+ *   wq[o,k] = clamp(round-half-even(W'[o,k] * (1.0f / dw[o])));  wsum[o] = sum_k wq[o,k];
+ *   inv_s[k] = 1.0f / s[k].
+ *   w_dev [N, K] fp32 (16-byte aligned, K a multiple of 16); s_dev [K] or NULL (= ones);
+ *   wq_dev [N, K] int8; dw_dev [N] fp32; wsum_dev [N] int32; inv_s_dev [K] fp32 or NULL. */
+STWQ_API int gps_fold_weights(const float* w_dev, const float* s_dev, int N, int K, int w_bits,
+                     int8_t* wq_dev, float* dw_dev, int32_t* wsum_dev, float* inv_s_dev,
+                     void* stream);
+
+/* Eq. 1 with the static parameters of each row's token position (Section 4.2), stored as int8.
+ *   x_dev [M, K] fp32 (16-byte aligned, K a multiple of 16); t = m mod L;
+ *   inv_s_dev [K] or NULL; inv_delta_dev [L] fp32; zp_dev [L] int32 (the z_t of Eq. 1, 0 .. 2^b - 1);
+ *   q_dev [M, K] int8 (16-byte aligned).
+ * A decode step whose rows all sit at position t passes L = 1 and the table pointers offset by t. */
+STWQ_API int stwq_quantize_act(const float* x_dev, int64_t M, int K, int L,
+                      const float* inv_s_dev, const float* inv_delta_dev, const int32_t* zp_dev,
+                      int a_bits, int8_t* q_dev, void* stream);
+
+/* The quantized linear layer: integer product and dequantization (Appendix A.1) into bf16.
+ *   acc[m,o] = sum_k q[m,k] * wq[o,k]                                  (int32, exact)
+ *   y[m,o]   = bf16( float(acc[m,o] - (zp[t] - off) * wsum[o]) * (delta[t] * dw[o]) + bias[o] )
+ * with t = m mod L and off = 128 for a_bits = 8, 0 for a_bits = 6.
+ *   q_dev [M, K] int8, wq_dev [N, K] int8 (both 16-byte aligned, K a multiple of 16, K <= 65536);
+ *   dw_dev [N] fp32; wsum_dev [N] int32; delta_dev [L] fp32; zp_dev [L] int32;
+ *   bias_dev [N] fp32 or NULL; y_bf16_dev [M, N] bf16 bit patterns, N a multiple of 8;
+ *   acc_dbg_dev [M, N] int32 or NULL: when given, also receives the raw accumulators.
+ * The schedule (MFMA-bound tiles for large M, weight-streaming tiles for small M) is chosen from
+ * the shape.  Decode: L = 1 with delta_dev / zp_dev offset by t. */
+STWQ_API int stwq_linear(const int8_t* q_dev, int64_t M, int K, int N, int L,
+                const int8_t* wq_dev, const float* dw_dev, const int32_t* wsum_dev,
+                const float* delta_dev, const int32_t* zp_dev, int a_bits,
+                const float* bias_dev,
+                uint16_t* y_bf16_dev, int32_t* acc_dbg_dev, void* stream);
+
+/* stwq_linear with the schedule named instead of chosen from the shape (same arguments, same
+ * results; the integer part is bit-identical across schedules):
+ *   STWQ_SCHEDULE_AUTO     what stwq_linear does;
+ *   STWQ_SCHEDULE_GENERIC  one wave per 32 x 32 tile straight from global memory, any valid shape;
+ *   STWQ_SCHEDULE_PREFILL  256 x 256 LDS-staged MFMA tiles, needs K a multiple of 128;
+ *   STWQ_SCHEDULE_DECODE   weight-streaming tiles for M <= 256, needs K a multiple of 128.
+ * A schedule that cannot take the shape returns STWQ_EUNSUPPORTED. */
+#define STWQ_SCHEDULE_AUTO    0
+#define STWQ_SCHEDULE_GENERIC 1
+#define STWQ_SCHEDULE_PREFILL 2
+#define STWQ_SCHEDULE_DECODE  3
+STWQ_API int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,
+                   const int8_t* wq_dev, const float* dw_dev, const int32_t* wsum_dev,
+                   const float* delta_dev, const int32_t* zp_dev, int a_bits,
+                   const float* bias_dev,
+                   uint16_t* y_bf16_dev, int32_t* acc_dbg_dev, int schedule, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STWQ_H */

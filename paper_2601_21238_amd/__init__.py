@@ -1,0 +1,11 @@
+"""MI355X-native STWQ + GPS quantized linear layer (PTQ4ARVG, arXiv 2601.21238).
+
+The work is done by libstwq.so (hand-written HIP for gfx950, C ABI in include/stwq.h); this package
+is the thin binding.  There is no CPU fallback: importing `binding` symbols that need the library
+raises if it has not been built (python -m paper_2601_21238_amd.build).
+"""
+from .binding import (  # noqa: F401
+    SCHEDULE_AUTO, SCHEDULE_DECODE, SCHEDULE_GENERIC, SCHEDULE_PREFILL, StwqError,
+    gps_fold_weights, lib, library_path, stwq_calibrate_stats, stwq_finalize_act_params,
+    stwq_linear, stwq_quantize_act, version,
+)

@@ -1,0 +1,153 @@
+"""ctypes binding of libstwq.so.  Argument marshalling only: shapes, dtypes, devices and
+contiguity are checked here, every computation runs in the library's kernels.
+
+Device functions take torch tensors (torch is used for device memory and streams only) and
+enqueue on torch's current stream of the tensors' device.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libstwq.so")
+_lib = None
+
+SCHEDULE_AUTO, SCHEDULE_GENERIC, SCHEDULE_PREFILL, SCHEDULE_DECODE = 0, 1, 2, 3
+
+EXPORTS = ("stwq_last_error", "stwq_version", "stwq_calibrate_stats", "stwq_finalize_act_params",
+           "gps_fold_weights", "stwq_quantize_act", "stwq_linear", "stwq_linear_ex")
+
+
+class StwqError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libstwq error {code}: {message}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """Loads libstwq.so (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2601_21238_amd.build` "
+                           "(there is no fallback path)")
+    l = C.CDLL(_LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
+    l.stwq_last_error.restype = C.c_char_p
+    l.stwq_last_error.argtypes = []
+    l.stwq_version.restype = C.c_char_p
+    l.stwq_version.argtypes = []
+    l.stwq_calibrate_stats.restype = i32
+    l.stwq_calibrate_stats.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    l.stwq_finalize_act_params.restype = i32
+    l.stwq_finalize_act_params.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    l.gps_fold_weights.restype = i32
+    l.gps_fold_weights.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
+    l.stwq_quantize_act.restype = i32
+    l.stwq_quantize_act.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp]
+    l.stwq_linear.restype = i32
+    l.stwq_linear.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    l.stwq_linear_ex.restype = i32
+    l.stwq_linear_ex.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
+    _lib = l
+    return l
+
+
+def version() -> str:
+    return lib().stwq_version().decode()
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise StwqError(code, lib().stwq_last_error().decode())
+
+
+def _dev(t, dtype, shape: Optional[Tuple[int, ...]], name: str, optional: bool = False):
+    """data_ptr of a contiguous device tensor of the given dtype/shape (None -> NULL)."""
+    import torch
+    if t is None:
+        if optional:
+            return None
+        raise ValueError(f"{name} is required")
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream(t) -> int:
+    import torch
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def stwq_calibrate_stats(x, L: int, inv_s=None, pos_min=None, pos_max=None,
+                         ch_min=None, ch_max=None, ch_absmax=None) -> None:
+    """Merges the statistics of x [rows, C] into the given (pre-initialised) device buffers."""
+    import torch
+    rows, Cn = x.shape
+    _check(lib().stwq_calibrate_stats(
+        _dev(x, torch.float32, None, "x"), rows, L, Cn,
+        _dev(inv_s, torch.float32, (Cn,), "inv_s", True),
+        _dev(pos_min, torch.float32, (L,), "pos_min", True), _dev(pos_max, torch.float32, (L,), "pos_max", True),
+        _dev(ch_min, torch.float32, (Cn,), "ch_min", True), _dev(ch_max, torch.float32, (Cn,), "ch_max", True),
+        _dev(ch_absmax, torch.float32, (Cn,), "ch_absmax", True), _stream(x)))
+
+
+def stwq_finalize_act_params(pos_min: np.ndarray, pos_max: np.ndarray, a_bits: int):
+    """Host helper: (delta, inv_delta, zp) numpy arrays from per-position min / max."""
+    pmin = np.ascontiguousarray(pos_min, dtype=np.float32)
+    pmax = np.ascontiguousarray(pos_max, dtype=np.float32)
+    if pmin.ndim != 1 or pmin.shape != pmax.shape:
+        raise ValueError("pos_min and pos_max must be 1-D arrays of the same length")
+    L = pmin.shape[0]
+    delta = np.empty(L, np.float32)
+    inv_delta = np.empty(L, np.float32)
+    zp = np.empty(L, np.int32)
+    _check(lib().stwq_finalize_act_params(pmin.ctypes.data, pmax.ctypes.data, L, a_bits,
+                                          delta.ctypes.data, inv_delta.ctypes.data, zp.ctypes.data))
+    return delta, inv_delta, zp
+
+
+def gps_fold_weights(w, s, w_bits: int, wq, dw, wsum, inv_s=None) -> None:
+    import torch
+    N, K = w.shape
+    _check(lib().gps_fold_weights(
+        _dev(w, torch.float32, None, "w"), _dev(s, torch.float32, (K,), "s", True), N, K, w_bits,
+        _dev(wq, torch.int8, (N, K), "wq"), _dev(dw, torch.float32, (N,), "dw"),
+        _dev(wsum, torch.int32, (N,), "wsum"), _dev(inv_s, torch.float32, (K,), "inv_s", True), _stream(w)))
+
+
+def stwq_quantize_act(x, L: int, inv_s, inv_delta, zp, a_bits: int, q) -> None:
+    import torch
+    M, K = x.shape
+    _check(lib().stwq_quantize_act(
+        _dev(x, torch.float32, None, "x"), M, K, L, _dev(inv_s, torch.float32, (K,), "inv_s", True),
+        _dev(inv_delta, torch.float32, (L,), "inv_delta"), _dev(zp, torch.int32, (L,), "zp"), a_bits,
+        _dev(q, torch.int8, (M, K), "q"), _stream(x)))
+
+
+def stwq_linear(q, wq, dw, wsum, delta, zp, a_bits: int, bias, y, L: int, acc_dbg=None,
+                schedule: int = SCHEDULE_AUTO) -> None:
+    import torch
+    M, K = q.shape
+    N = wq.shape[0]
+    _check(lib().stwq_linear_ex(
+        _dev(q, torch.int8, None, "q"), M, K, N, L, _dev(wq, torch.int8, (N, K), "wq"),
+        _dev(dw, torch.float32, (N,), "dw"), _dev(wsum, torch.int32, (N,), "wsum"),
+        _dev(delta, torch.float32, (L,), "delta"), _dev(zp, torch.int32, (L,), "zp"), a_bits,
+        _dev(bias, torch.float32, (N,), "bias", True), _dev(y, torch.bfloat16, (M, N), "y"),
+        _dev(acc_dbg, torch.int32, (M, N), "acc_dbg", True), schedule, _stream(q)))

@@ -1,0 +1,75 @@
+// Internal helpers shared by the HIP translation units of libstwq (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "stwq.h"
+
+namespace stwq {
+
+// Records a message for stwq_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define STWQ_REQUIRE(cond, ...)                                   \
+    do {                                                          \
+        if (!(cond)) return ::stwq::fail(STWQ_EINVAL, __VA_ARGS__); \
+    } while (0)
+
+#define STWQ_HIP(expr)                                                                         \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return ::stwq::fail(STWQ_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));      \
+    } while (0)
+
+// Returns STWQ_OK or records the error of the most recent launch.
+inline int launch_status(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(STWQ_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+    return STWQ_OK;
+}
+
+// ---- device helpers -------------------------------------------------------------------------
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Exact float min / max merged into global memory.  IEEE floats order like sign-magnitude
+// integers: non-negative values compare as signed ints, negative values in reverse as unsigned.
+// -0 is canonicalised to +0 first so that it takes the non-negative branch with the right bits.
+__device__ __forceinline__ void atomic_min_f32(float* addr, float v) {
+    if (v == 0.0f) v = 0.0f;
+    if (v >= 0.0f) atomicMin(reinterpret_cast<int*>(addr), __float_as_int(v));
+    else atomicMax(reinterpret_cast<unsigned*>(addr), __float_as_uint(v));
+}
+__device__ __forceinline__ void atomic_max_f32(float* addr, float v) {
+    if (v == 0.0f) v = 0.0f;
+    if (v >= 0.0f) atomicMax(reinterpret_cast<int*>(addr), __float_as_int(v));
+    else atomicMin(reinterpret_cast<unsigned*>(addr), __float_as_uint(v));
+}
+
+// Eq. 1 with precomputed reciprocals: two multiplies, round half to even, add z, clamp.
+// `pre` is x already multiplied by the channel's reciprocal scale.
+__device__ __forceinline__ int quant_code(float pre, float inv_delta, float zf, float qmax) {
+    float r = rintf(pre * inv_delta);
+    return static_cast<int>(fminf(fmaxf(r + zf, 0.0f), qmax));
+}
+
+}  // namespace stwq

@@ -1,0 +1,52 @@
+// Host-only part of libstwq: error reporting and the per-position parameter finaliser.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "common.h"
+
+namespace stwq {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+}  // namespace stwq
+
+extern "C" const char* stwq_last_error(void) { return stwq::g_err; }
+
+extern "C" const char* stwq_version(void) { return "stwq-gfx950 0.1"; }
+
+// Eq. 1 (Section 3): delta = R / (2^b - 1), z = round(-x_down / delta), with the range widened to
+// contain zero and the reciprocal of delta made once here (the device multiplies by it).
+// This file is compiled with -ffp-contract=off: every fp32 operation below rounds once.
+extern "C" int stwq_finalize_act_params(const float* pos_min, const float* pos_max, int L, int a_bits,
+                                        float* delta, float* inv_delta, int32_t* zp) {
+    stwq::clear_error();
+    STWQ_REQUIRE(pos_min && pos_max && delta && inv_delta && zp, "stwq_finalize_act_params: null pointer");
+    STWQ_REQUIRE(L > 0, "stwq_finalize_act_params: L = %d must be positive", L);
+    STWQ_REQUIRE(a_bits == 8 || a_bits == 6, "stwq_finalize_act_params: a_bits = %d, expected 6 or 8", a_bits);
+    const float qmax = static_cast<float>((1 << a_bits) - 1);
+    for (int t = 0; t < L; ++t) {
+        STWQ_REQUIRE(std::isfinite(pos_min[t]) && std::isfinite(pos_max[t]),
+                     "stwq_finalize_act_params: position %d has non-finite statistics", t);
+        const float lo = std::fmin(pos_min[t], 0.0f);
+        const float hi = std::fmax(pos_max[t], 0.0f);
+        const float range = std::fmax(hi - lo, 1e-8f);
+        const float d = range / qmax;
+        const float inv = 1.0f / d;
+        const float z = std::nearbyintf(-lo * inv);      // default rounding mode: ties to even
+        delta[t] = d;
+        inv_delta[t] = inv;
+        zp[t] = static_cast<int32_t>(std::fmin(std::fmax(z, 0.0f), qmax));
+    }
+    return STWQ_OK;
+}

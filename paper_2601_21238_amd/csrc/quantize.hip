@@ -1,0 +1,81 @@
+// Activation quantization with static per-position parameters (Eq. 1; Section 4.2).
+//
+// HBM-bound: 4 B read + 1 B written per element.  A block handles kRows consecutive rows; a thread
+// converts one float4 per row and step into four packed codes (coalesced 16-byte loads, 4-byte
+// stores), with the rows' loads issued together so several requests per thread are in flight.
+#include "common.h"
+
+namespace stwq {
+
+constexpr int kQuantThreads = 256;
+constexpr int kQuantRows = 4;
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
+    const float* __restrict__ x, long long M, int K, int L,
+    const float* __restrict__ inv_s, const float* __restrict__ inv_delta, const int32_t* __restrict__ zp,
+    float qmax, int off, int8_t* __restrict__ q) {
+    const int tid = threadIdx.x;
+    const int k4n = K >> 2;
+    const long long m0 = static_cast<long long>(blockIdx.x) * kQuantRows;
+
+    float id[kQuantRows], zf[kQuantRows];
+    const f4* xr[kQuantRows];
+    bool valid[kQuantRows];
+    uint32_t* qr[kQuantRows];
+#pragma unroll
+    for (int r = 0; r < kQuantRows; ++r) {
+        long long m = m0 + r;
+        valid[r] = m < M;
+        if (!valid[r]) m = M - 1;                    // ragged tail: load a valid row, store nothing
+        const int t = static_cast<int>(m % L);
+        id[r] = inv_delta[t];
+        zf[r] = static_cast<float>(zp[t]);
+        xr[r] = reinterpret_cast<const f4*>(x + m * K);
+        qr[r] = reinterpret_cast<uint32_t*>(q + m * K);
+    }
+    const float4* s4 = reinterpret_cast<const float4*>(inv_s);
+
+    for (int k4 = tid; k4 < k4n; k4 += kQuantThreads) {
+        f4 v[kQuantRows];
+#pragma unroll
+        for (int r = 0; r < kQuantRows; ++r) v[r] = __builtin_nontemporal_load(xr[r] + k4);
+        float4 sv = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (inv_s) sv = s4[k4];
+#pragma unroll
+        for (int r = 0; r < kQuantRows; ++r) {
+            f4 p = v[r];
+            if (inv_s) { p.x *= sv.x; p.y *= sv.y; p.z *= sv.z; p.w *= sv.w; }
+            const int a = quant_code(p.x, id[r], zf[r], qmax) - off;
+            const int b = quant_code(p.y, id[r], zf[r], qmax) - off;
+            const int c = quant_code(p.z, id[r], zf[r], qmax) - off;
+            const int d = quant_code(p.w, id[r], zf[r], qmax) - off;
+            if (valid[r])
+                qr[r][k4] = (static_cast<uint32_t>(a) & 0xFFu) | ((static_cast<uint32_t>(b) & 0xFFu) << 8) |
+                            ((static_cast<uint32_t>(c) & 0xFFu) << 16) | (static_cast<uint32_t>(d) << 24);
+        }
+    }
+}
+
+}  // namespace stwq
+
+extern "C" int stwq_quantize_act(const float* x_dev, int64_t M, int K, int L,
+                                 const float* inv_s_dev, const float* inv_delta_dev, const int32_t* zp_dev,
+                                 int a_bits, int8_t* q_dev, void* stream) {
+    using namespace stwq;
+    clear_error();
+    STWQ_REQUIRE(x_dev && inv_delta_dev && zp_dev && q_dev, "stwq_quantize_act: null pointer");
+    STWQ_REQUIRE(M > 0 && K > 0 && L > 0, "stwq_quantize_act: M = %lld, K = %d, L = %d must be positive",
+                 static_cast<long long>(M), K, L);
+    STWQ_REQUIRE(K % 16 == 0, "stwq_quantize_act: K = %d must be a multiple of 16", K);
+    STWQ_REQUIRE(a_bits == 8 || a_bits == 6, "stwq_quantize_act: a_bits = %d, expected 6 or 8", a_bits);
+    STWQ_REQUIRE(aligned16(x_dev) && aligned16(q_dev) && (!inv_s_dev || aligned16(inv_s_dev)),
+                 "stwq_quantize_act: x_dev, inv_s_dev and q_dev must be 16-byte aligned");
+    const long long blocks = (M + kQuantRows - 1) / kQuantRows;
+    STWQ_REQUIRE(blocks <= 0x7FFFFFFFLL, "stwq_quantize_act: M = %lld is too large", static_cast<long long>(M));
+    const float qmax = static_cast<float>((1 << a_bits) - 1);
+    const int off = a_bits == 8 ? 128 : 0;
+    quantize_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kQuantThreads), 0, static_cast<hipStream_t>(stream)>>>(
+        x_dev, M, K, L, inv_s_dev, inv_delta_dev, zp_dev, qmax, off, q_dev);
+    return launch_status("quantize_kernel");
+}

@@ -1,0 +1,162 @@
+// Calibration statistics: per-position min / max of x * inv_s and per-channel min / max / absmax
+// of x (ranges of Eq. 1; range step of the GPS algorithm; Section 4.2 offline calibration).
+//
+// HBM-bound: every element is read once (4 B).  A block owns a 1024-channel slab (one float4 per
+// thread) and a strided set of token positions; for one position it walks all samples, so the
+// per-position reduction happens once per (position, block) and channel statistics stay in
+// registers until the block ends.  Merging into the caller's buffers uses integer atomics on the
+// float bit patterns, which is exact and order-independent.
+#include "common.h"
+
+namespace stwq {
+
+constexpr int kStatsThreads = 256;
+constexpr int kStatsSlab = kStatsThreads * 4;   // channels per block
+
+template <bool POS, bool CH>
+__global__ __launch_bounds__(kStatsThreads) void stats_kernel(
+    const float* __restrict__ x, int n_samples, int samples_per_z, int L, int C, const float* __restrict__ inv_s,
+    float* __restrict__ pos_min, float* __restrict__ pos_max,
+    float* __restrict__ ch_min, float* __restrict__ ch_max, float* __restrict__ ch_absmax) {
+    __shared__ float red_min[kStatsThreads / 64];
+    __shared__ float red_max[kStatsThreads / 64];
+
+    const int tid = threadIdx.x;
+    const int c0 = blockIdx.y * kStatsSlab + tid * 4;
+    const bool active = c0 < C;
+    const float inf = __builtin_inff();
+
+    float4 is = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (POS && active && inv_s) is = *reinterpret_cast<const float4*>(inv_s + c0);
+
+    float4 cmin = make_float4(inf, inf, inf, inf);
+    float4 cmax = make_float4(-inf, -inf, -inf, -inf);
+
+    const int n_begin = blockIdx.z * samples_per_z;
+    const int n_end = min(n_begin + samples_per_z, n_samples);
+    const size_t row_stride = static_cast<size_t>(C);
+    const size_t sample_stride = static_cast<size_t>(L) * row_stride;
+
+    for (int t = blockIdx.x; t < L; t += gridDim.x) {
+        float pmin = inf, pmax = -inf;
+        if (active) {
+            const float* p = x + static_cast<size_t>(t) * row_stride + c0;
+            int n = n_begin;
+            for (; n + 4 <= n_end; n += 4) {
+                float4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    v[u] = *reinterpret_cast<const float4*>(p + static_cast<size_t>(n + u) * sample_stride);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (CH) {
+                        cmin.x = fminf(cmin.x, v[u].x); cmax.x = fmaxf(cmax.x, v[u].x);
+                        cmin.y = fminf(cmin.y, v[u].y); cmax.y = fmaxf(cmax.y, v[u].y);
+                        cmin.z = fminf(cmin.z, v[u].z); cmax.z = fmaxf(cmax.z, v[u].z);
+                        cmin.w = fminf(cmin.w, v[u].w); cmax.w = fmaxf(cmax.w, v[u].w);
+                    }
+                    if (POS) {
+                        const float a = v[u].x * is.x, b = v[u].y * is.y, c = v[u].z * is.z, d = v[u].w * is.w;
+                        pmin = fminf(pmin, fminf(fminf(a, b), fminf(c, d)));
+                        pmax = fmaxf(pmax, fmaxf(fmaxf(a, b), fmaxf(c, d)));
+                    }
+                }
+            }
+            for (; n < n_end; ++n) {
+                const float4 v = *reinterpret_cast<const float4*>(p + static_cast<size_t>(n) * sample_stride);
+                if (CH) {
+                    cmin.x = fminf(cmin.x, v.x); cmax.x = fmaxf(cmax.x, v.x);
+                    cmin.y = fminf(cmin.y, v.y); cmax.y = fmaxf(cmax.y, v.y);
+                    cmin.z = fminf(cmin.z, v.z); cmax.z = fmaxf(cmax.z, v.z);
+                    cmin.w = fminf(cmin.w, v.w); cmax.w = fmaxf(cmax.w, v.w);
+                }
+                if (POS) {
+                    const float a = v.x * is.x, b = v.y * is.y, c = v.z * is.z, d = v.w * is.w;
+                    pmin = fminf(pmin, fminf(fminf(a, b), fminf(c, d)));
+                    pmax = fmaxf(pmax, fmaxf(fmaxf(a, b), fmaxf(c, d)));
+                }
+            }
+        }
+        if (POS) {
+            pmin = wave_min(pmin);
+            pmax = wave_max(pmax);
+            if ((tid & 63) == 0) { red_min[tid >> 6] = pmin; red_max[tid >> 6] = pmax; }
+            __syncthreads();
+            if (tid == 0) {
+                float a = red_min[0], b = red_max[0];
+#pragma unroll
+                for (int w = 1; w < kStatsThreads / 64; ++w) { a = fminf(a, red_min[w]); b = fmaxf(b, red_max[w]); }
+                if (a <= b) {   // false only if this slab held no channel
+                    atomic_min_f32(pos_min + t, a);
+                    atomic_max_f32(pos_max + t, b);
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    if (CH && active) {
+        const float mn[4] = {cmin.x, cmin.y, cmin.z, cmin.w};
+        const float mx[4] = {cmax.x, cmax.y, cmax.z, cmax.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (mn[j] > mx[j]) continue;   // this block saw no row
+            if (ch_min) atomic_min_f32(ch_min + c0 + j, mn[j]);
+            if (ch_max) atomic_max_f32(ch_max + c0 + j, mx[j]);
+            if (ch_absmax) atomic_max_f32(ch_absmax + c0 + j, fmaxf(fabsf(mn[j]), fabsf(mx[j])));
+        }
+    }
+}
+
+}  // namespace stwq
+
+extern "C" int stwq_calibrate_stats(const float* x_dev, int64_t rows, int L, int C,
+                                    const float* inv_s_dev,
+                                    float* pos_min_dev, float* pos_max_dev,
+                                    float* ch_min_dev, float* ch_max_dev, float* ch_absmax_dev,
+                                    void* stream) {
+    using namespace stwq;
+    clear_error();
+    STWQ_REQUIRE(x_dev, "stwq_calibrate_stats: x_dev is null");
+    STWQ_REQUIRE(L > 0 && C > 0 && rows > 0, "stwq_calibrate_stats: rows = %lld, L = %d, C = %d must be positive",
+                 static_cast<long long>(rows), L, C);
+    STWQ_REQUIRE(rows % L == 0, "stwq_calibrate_stats: rows = %lld is not a multiple of L = %d",
+                 static_cast<long long>(rows), L);
+    STWQ_REQUIRE(rows / L <= INT32_MAX, "stwq_calibrate_stats: too many samples");
+    STWQ_REQUIRE(C % 4 == 0, "stwq_calibrate_stats: C = %d must be a multiple of 4", C);
+    STWQ_REQUIRE(aligned16(x_dev) && (!inv_s_dev || aligned16(inv_s_dev)),
+                 "stwq_calibrate_stats: x_dev and inv_s_dev must be 16-byte aligned");
+    STWQ_REQUIRE((pos_min_dev == nullptr) == (pos_max_dev == nullptr),
+                 "stwq_calibrate_stats: give both pos_min_dev and pos_max_dev or neither");
+    const bool pos = pos_min_dev != nullptr;
+    const bool ch = ch_min_dev || ch_max_dev || ch_absmax_dev;
+    STWQ_REQUIRE(pos || ch, "stwq_calibrate_stats: no output buffer given");
+
+    const int n_samples = static_cast<int>(rows / L);
+    const int slabs = (C + kStatsSlab - 1) / kStatsSlab;
+    int gx = 2048 / slabs;                 // about eight 256-thread blocks per CU over 256 CUs
+    if (gx < 1) gx = 1;
+    if (gx > L) gx = L;
+    // few positions (a decode table slice, L = 1): split the samples over blockIdx.z instead
+    int gz = 1;
+    if (gx * slabs < 1024) {
+        gz = 2048 / (gx * slabs);
+        const int max_gz = (n_samples + 7) / 8;      // at least eight samples per block
+        if (gz > max_gz) gz = max_gz;
+        if (gz < 1) gz = 1;
+    }
+    const int spz = (n_samples + gz - 1) / gz;
+    gz = (n_samples + spz - 1) / spz;
+    dim3 grid(gx, slabs, gz), block(kStatsThreads);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (pos && ch)
+        stats_kernel<true, true><<<grid, block, 0, s>>>(x_dev, n_samples, spz, L, C, inv_s_dev, pos_min_dev, pos_max_dev,
+                                                        ch_min_dev, ch_max_dev, ch_absmax_dev);
+    else if (pos)
+        stats_kernel<true, false><<<grid, block, 0, s>>>(x_dev, n_samples, spz, L, C, inv_s_dev, pos_min_dev, pos_max_dev,
+                                                         nullptr, nullptr, nullptr);
+    else
+        stats_kernel<false, true><<<grid, block, 0, s>>>(x_dev, n_samples, spz, L, C, nullptr, nullptr, nullptr,
+                                                         ch_min_dev, ch_max_dev, ch_absmax_dev);
+    return launch_status("stats_kernel");
+}

@@ -1,0 +1,90 @@
+"""One STWQ + GPS quantized linear layer on the GPU: the order of library calls for the offline
+stage (statistics -> fold -> statistics of the scaled input -> per-position parameters) and the
+online stage (quantize -> linear).  No arithmetic happens here.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class StwqLinear:
+    """Device-resident parameters of one quantized linear layer (weights [N, K], L positions)."""
+
+    def __init__(self, N: int, K: int, L: int, a_bits: int = 8, w_bits: int = 8, device="cuda:0"):
+        self.N, self.K, self.L, self.a_bits, self.w_bits = N, K, L, a_bits, w_bits
+        self.device = torch.device(device)
+        d = self.device
+        self.wq = torch.empty((N, K), dtype=torch.int8, device=d)
+        self.dw = torch.empty(N, dtype=torch.float32, device=d)
+        self.wsum = torch.empty(N, dtype=torch.int32, device=d)
+        self.inv_s: Optional[torch.Tensor] = None
+        self.bias: Optional[torch.Tensor] = None
+        self.pos_min = torch.full((L,), float("inf"), dtype=torch.float32, device=d)
+        self.pos_max = torch.full((L,), float("-inf"), dtype=torch.float32, device=d)
+        self.delta = torch.empty(L, dtype=torch.float32, device=d)
+        self.inv_delta = torch.empty(L, dtype=torch.float32, device=d)
+        self.zp = torch.empty(L, dtype=torch.int32, device=d)
+
+    # ---- offline -------------------------------------------------------------------------
+    def channel_stats(self, x_calib: torch.Tensor):
+        """Per-channel (min, max, absmax) of raw calibration activations, as device tensors."""
+        d = self.device
+        ch_min = torch.full((self.K,), float("inf"), dtype=torch.float32, device=d)
+        ch_max = torch.full((self.K,), float("-inf"), dtype=torch.float32, device=d)
+        ch_abs = torch.zeros(self.K, dtype=torch.float32, device=d)
+        B.stwq_calibrate_stats(x_calib, self.L, ch_min=ch_min, ch_max=ch_max, ch_absmax=ch_abs)
+        return ch_min, ch_max, ch_abs
+
+    def fold(self, w: torch.Tensor, s: Optional[torch.Tensor], bias: Optional[torch.Tensor]) -> None:
+        """Eq. 2 folding and weight quantization; keeps 1/s for the activation side."""
+        self.inv_s = torch.empty(self.K, dtype=torch.float32, device=self.device) if s is not None else None
+        B.gps_fold_weights(w, s, self.w_bits, self.wq, self.dw, self.wsum, self.inv_s)
+        self.bias = bias
+
+    def accumulate_position_stats(self, x_calib: torch.Tensor) -> None:
+        """Streams one chunk of calibration activations (full sequences) into the per-position ranges."""
+        B.stwq_calibrate_stats(x_calib, self.L, inv_s=self.inv_s, pos_min=self.pos_min, pos_max=self.pos_max)
+
+    def finalize(self) -> None:
+        """Per-position (delta, 1/delta, z) from the accumulated ranges (host helper of the library)."""
+        delta, inv_delta, zp = B.stwq_finalize_act_params(self.pos_min.cpu().numpy(), self.pos_max.cpu().numpy(),
+                                                          self.a_bits)
+        self.delta.copy_(torch.from_numpy(delta))
+        self.inv_delta.copy_(torch.from_numpy(inv_delta))
+        self.zp.copy_(torch.from_numpy(zp))
+
+    def calibrate(self, x_calib: torch.Tensor, w: torch.Tensor, s: Optional[torch.Tensor],
+                  bias: Optional[torch.Tensor]) -> None:
+        self.fold(w, s, bias)
+        self.accumulate_position_stats(x_calib)
+        self.finalize()
+
+    # ---- online --------------------------------------------------------------------------
+    def quantize(self, x: torch.Tensor, q: Optional[torch.Tensor] = None, t0: Optional[int] = None) -> torch.Tensor:
+        if q is None:
+            q = torch.empty(x.shape, dtype=torch.int8, device=self.device)
+        if t0 is None:
+            B.stwq_quantize_act(x, self.L, self.inv_s, self.inv_delta, self.zp, self.a_bits, q)
+        else:   # decode step: every row sits at position t0
+            B.stwq_quantize_act(x, 1, self.inv_s, self.inv_delta[t0:t0 + 1], self.zp[t0:t0 + 1], self.a_bits, q)
+        return q
+
+    def linear(self, q: torch.Tensor, y: Optional[torch.Tensor] = None, acc_dbg: Optional[torch.Tensor] = None,
+               t0: Optional[int] = None, schedule: int = B.SCHEDULE_AUTO) -> torch.Tensor:
+        if y is None:
+            y = torch.empty((q.shape[0], self.N), dtype=torch.bfloat16, device=self.device)
+        if t0 is None:
+            B.stwq_linear(q, self.wq, self.dw, self.wsum, self.delta, self.zp, self.a_bits, self.bias, y, self.L,
+                          acc_dbg, schedule)
+        else:
+            B.stwq_linear(q, self.wq, self.dw, self.wsum, self.delta[t0:t0 + 1], self.zp[t0:t0 + 1], self.a_bits,
+                          self.bias, y, 1, acc_dbg, schedule)
+        return y
+
+    def forward(self, x: torch.Tensor, t0: Optional[int] = None) -> torch.Tensor:
+        return self.linear(self.quantize(x, t0=t0), t0=t0)

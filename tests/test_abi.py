@@ -1,0 +1,70 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
+before touching the GPU (runs without a device)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2601_21238_amd as P
+from paper_2601_21238_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "stwq.h")).read()
+    return re.findall(r"STWQ_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS) and len(names) >= 8
+    l = P.lib()
+    for n in names:
+        assert getattr(l, n) is not None
+    assert P.version().startswith("stwq-gfx950")
+
+
+def test_invalid_arguments_return_einval_without_a_gpu():
+    l = P.lib()
+    buf = (C.c_char * 4096)()
+    p = C.addressof(buf)
+    p = (p + 15) & ~15           # 16-byte aligned fake pointer; never dereferenced on these paths
+    EINVAL = -1
+    assert l.stwq_calibrate_stats(None, 8, 4, 16, None, p, p, None, None, None, None) == EINVAL
+    assert b"null" in l.stwq_last_error()
+    assert l.stwq_calibrate_stats(p, 9, 4, 16, None, p, p, None, None, None, None) == EINVAL       # rows % L
+    assert l.stwq_calibrate_stats(p, 8, 4, 18, None, p, p, None, None, None, None) == EINVAL       # C % 4
+    assert l.stwq_calibrate_stats(p, 8, 4, 16, None, p, None, None, None, None, None) == EINVAL    # one of a pair
+    assert l.stwq_calibrate_stats(p, 8, 4, 16, None, None, None, None, None, None, None) == EINVAL  # no output
+    assert l.stwq_calibrate_stats(p + 4, 8, 4, 16, None, p, p, None, None, None, None) == EINVAL   # alignment
+    assert l.gps_fold_weights(p, None, 4, 24, 8, p, p, p, None, None) == EINVAL                     # K % 16
+    assert l.gps_fold_weights(p, None, 4, 32, 7, p, p, p, None, None) == EINVAL                     # bits
+    assert l.gps_fold_weights(p, None, 0, 32, 8, p, p, p, None, None) == EINVAL
+    assert l.stwq_quantize_act(p, 4, 32, 0, None, p, p, 8, p, None) == EINVAL                       # L
+    assert l.stwq_quantize_act(p, 4, 32, 2, None, p, p, 4, p, None) == EINVAL                       # bits
+    assert l.stwq_quantize_act(p, 4, 32, 2, None, None, p, 8, p, None) == EINVAL
+    assert l.stwq_linear(p, 4, 32, 12, 2, p, p, p, p, p, 8, None, p, None, None) == EINVAL          # N % 8
+    assert l.stwq_linear(p, 4, 40, 16, 2, p, p, p, p, p, 8, None, p, None, None) == EINVAL          # K % 16
+    assert l.stwq_linear(p, 4, 1 << 17, 16, 2, p, p, p, p, p, 8, None, p, None, None) == EINVAL     # K too large
+    assert l.stwq_linear(p, 4, 32, 16, 2, p, p, p, p, p, 8, None, None, None, None) == EINVAL
+    assert l.stwq_linear_ex(p, 4, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 99, None) == EINVAL   # schedule
+    assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 2, None) == -2      # prefill needs K % 128
+    assert b"128" in l.stwq_last_error()
+
+
+def test_finalize_host_helper():
+    d, i, z = P.stwq_finalize_act_params(np.array([-0.5], np.float32), np.array([191 / 128], np.float32), 8)
+    assert d[0] == np.float32(1 / 128) and i[0] == 128 and z[0] == 64
+    with pytest.raises(P.StwqError):
+        P.stwq_finalize_act_params(np.array([np.nan], np.float32), np.array([1.0], np.float32), 8)
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    x = torch.zeros((4, 16))
+    with pytest.raises(ValueError):
+        P.stwq_quantize_act(x, 2, None, torch.zeros(2), torch.zeros(2, dtype=torch.int32), 8,
+                            torch.zeros((4, 16), dtype=torch.int8))

@@ -1,0 +1,165 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import stwq_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+import paper_2601_21238_amd as P            # noqa: E402
+from paper_2601_21238_amd.layer import StwqLinear   # noqa: E402
+import gpu_common as G                       # noqa: E402
+
+F32 = np.float32
+SCHEDULES = {"generic": P.SCHEDULE_GENERIC, "prefill": P.SCHEDULE_PREFILL}
+
+
+def small_spec(**kw):
+    base = wl.config_linears(2)[0]
+    return wl.shrink(base, **kw)
+
+
+# ---------------------------------------------------------------- statistics
+
+@pytest.mark.parametrize("L,C,n", [(7, 64, 5), (37, 1028, 9), (680, 1024, 4), (1, 2048, 301), (256, 5120, 3)])
+def test_calibrate_stats(L, C, n):
+    rng = np.random.default_rng(L * 1000 + C)
+    x = (rng.standard_normal((n * L, C)) * rng.uniform(0.5, 4, (1, C))).astype(F32)
+    x[rng.integers(0, n * L, 20), rng.integers(0, C, 20)] = 0.0
+    x[0, 0] = -0.0
+    inv_s = (1.0 / rng.uniform(0.5, 8, C)).astype(F32)
+    d = G.DEV
+    pos_min = torch.full((L,), float("inf"), device=d)
+    pos_max = torch.full((L,), float("-inf"), device=d)
+    ch_min = torch.full((C,), float("inf"), device=d)
+    ch_max = torch.full((C,), float("-inf"), device=d)
+    ch_abs = torch.zeros(C, device=d)
+    xd = G.dev(x)
+    # streamed in two calls (merge semantics); the second call also covers an odd sample count
+    cut = (n // 2) * L
+    for part in ([xd] if cut == 0 else [xd[:cut], xd[cut:]]):
+        P.stwq_calibrate_stats(part, L, inv_s=G.dev(inv_s), pos_min=pos_min, pos_max=pos_max,
+                               ch_min=ch_min, ch_max=ch_max, ch_absmax=ch_abs)
+    torch.cuda.synchronize()
+    r_min, r_max, r_abs = O.channel_stats(x)
+    p_min, p_max = O.position_stats(x, inv_s, L)
+    assert np.array_equal(G.host(ch_min), r_min) and np.array_equal(G.host(ch_max), r_max)
+    assert np.array_equal(G.host(ch_abs), r_abs)
+    assert np.array_equal(G.host(pos_min), p_min) and np.array_equal(G.host(pos_max), p_max)
+    # position statistics alone, no scale; all-negative and all-positive data keep their sign
+    for sign in (-1.0, 1.0):
+        xs = (np.abs(x) + F32(0.25)) * F32(sign)
+        pos_min.fill_(float("inf"))
+        pos_max.fill_(float("-inf"))
+        P.stwq_calibrate_stats(G.dev(xs), L, pos_min=pos_min, pos_max=pos_max)
+        p_min, p_max = O.position_stats(xs, None, L)
+        assert np.array_equal(G.host(pos_min), p_min) and np.array_equal(G.host(pos_max), p_max)
+
+
+def test_finalize_matches_oracle():
+    rng = np.random.default_rng(9)
+    for bits in (6, 8):
+        pmin = (-np.abs(rng.standard_normal(500)) * 5).astype(F32)
+        pmax = (np.abs(rng.standard_normal(500)) * 50).astype(F32)
+        pmin[:5] = [0.0, 1.0, -3.0, 0.0, -1e-12]
+        pmax[:5] = [0.0, 3.0, -1.0, 1e-30, 1e-12]
+        d, i, z = P.stwq_finalize_act_params(pmin, pmax, bits)
+        rd, ri, rz = O.act_params(pmin, pmax, bits)
+        assert np.array_equal(d, rd) and np.array_equal(i, ri) and np.array_equal(z, rz)
+
+
+# ---------------------------------------------------------------- fold
+
+@pytest.mark.parametrize("N,K,bits,with_s", [(8, 16, 8, True), (72, 160, 6, True), (1024, 1024, 8, True),
+                                              (40, 4096, 8, False), (24, 12288, 6, True)])
+def test_fold_weights(N, K, bits, with_s):
+    rng = np.random.default_rng(N + K)
+    w = (rng.standard_normal((N, K)) * 0.02).astype(F32)
+    w[min(3, N - 1)] = 0
+    s = rng.uniform(0.05, 120, K).astype(F32) if with_s else None
+    layer = StwqLinear(N, K, 4, bits, bits, G.DEV)
+    layer.fold(G.dev(w), None if s is None else G.dev(s), None)
+    torch.cuda.synchronize()
+    wf, inv_s = O.fold_weights(w, s)
+    wq, dw, wsum = O.quantize_weights(wf, bits)
+    assert np.array_equal(G.host(layer.wq), wq)
+    assert np.array_equal(G.host(layer.dw), dw)
+    assert np.array_equal(G.host(layer.wsum), wsum)
+    if with_s:
+        assert np.array_equal(G.host(layer.inv_s), inv_s)
+
+
+# ---------------------------------------------------------------- whole layer, small shapes
+
+CASES = [
+    # name,            K,    N,   L,  batch, calib, bits, schedules
+    ("tiny",           16,   8,   3,  1,     4,     8,    ("generic",)),
+    ("k_tail16",       144,  72,  37, 3,     6,     8,    ("generic",)),
+    ("ragged_generic", 160,  200, 37, 5,     6,     6,    ("generic",)),
+    ("ragged_tiles",   256,  328, 131, 5,    6,     8,    ("generic", "prefill")),
+    ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "prefill")),
+    ("one_tile",       128,  256, 64, 4,     6,     8,    ("prefill",)),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: c[0])
+def test_layer_small(case):
+    name, K, N, L, batch, n_calib, bits, schedules = case
+    spec = small_spec(K=K, N=N, L=L, batch=batch, n_calib=n_calib, a_bits=bits, w_bits=bits,
+                      n_outliers=min(8, K // 8))
+    w, b, xc, xt = G.make_case(spec)
+    pack = G.oracle_pack(spec, xc, w, b)
+    layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+    G.check_calibration(layer, pack)
+    for sch in schedules:
+        G.check_forward(layer, pack, xt, SCHEDULES[sch], what=f"{name}/{sch}")
+    # decode form: rows all at one position
+    t0 = L // 2
+    G.check_forward(layer, pack, xt[t0::L][:1] if batch == 1 else xt[t0::L], SCHEDULES["generic"], t0=t0,
+                    what=f"{name}/decode-form")
+
+
+def test_config1_full():
+    """Configuration 1 at full size: 680 x 1024 -> 1024, W8A8, GPS scale from 32 calibration samples."""
+    spec = wl.config_linears(1)[0]
+    w, b, xc, xt = G.make_case(spec)
+    pack = G.oracle_pack(spec, xc, w, b)
+    layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+    G.check_calibration(layer, pack)
+    results = {}
+    for sch in ("generic", "prefill"):
+        results[sch] = G.check_forward(layer, pack, xt, SCHEDULES[sch], what=f"config1/{sch}")
+    # run-to-run determinism and schedule independence of the integer part
+    q2, acc2, y2 = G.check_forward(layer, pack, xt, SCHEDULES["prefill"], what="config1/prefill again")
+    assert torch.equal(acc2, results["prefill"][1]) and torch.equal(y2, results["prefill"][2])
+    assert torch.equal(results["generic"][1], results["prefill"][1])
+    # auto picks a schedule and agrees
+    y_auto = layer.forward(G.dev(xt))
+    assert torch.equal(y_auto, y2)
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+def test_edge_inputs(bits):
+    spec = small_spec(K=256, N=264, L=19, batch=15, n_calib=8, a_bits=bits, w_bits=bits)
+    w, b, xc, xt = G.make_case(spec)
+    pack = G.oracle_pack(spec, xc, w, b)
+    layer = G.gpu_layer(spec, xc, w, None, pack["s"])         # no bias
+    pack["bias"] = None
+    # zeros -> code z, output 0; huge values -> both clamp ends; tiny (denormal) values
+    x = xt.copy()
+    x[0] = 0
+    x[1] = 1e30
+    x[2] = -1e30
+    x[3] = 1e-42
+    x[4, ::2] = np.inf
+    x[4, 1::2] = -np.inf
+    for sch in ("generic", "prefill"):
+        q, acc, y = G.check_forward(layer, pack, x, SCHEDULES[sch], what=f"edges/{sch}")
+        assert not y[0].float().abs().max().item() > 0
+    codes = G.host(q).astype(np.int32) + O.store_offset(bits)
+    assert codes[1].max() == O.qmax_act(bits) and codes[2].min() == 0
+    # a single row
+    G.check_forward(layer, pack, xt[:1], SCHEDULES["generic"], what="one row")
+    G.check_forward(layer, pack, xt[:1], P.SCHEDULE_AUTO, what="one row/auto")
