@@ -101,67 +101,138 @@ __global__ __launch_bounds__(kSimpleThreads) void linear_simple_kernel(LinearArg
 }
 
 // ------------------------------------------------------------------------------------------------
-// Prefill kernel: 256 (output channels) x 256 (tokens) block tile, K step 128, 8 waves in a
-// 2 x 4 grid (wave tile 128 x 64 = 4 x 2 MFMA tiles, 128 int32 accumulators per lane).  Both
-// operand tiles are staged in LDS by direct global -> LDS loads (no register staging), double
-// buffered; MFMA operands are read back with ds_read_b128.
+// Prefill kernel: 256 (output channels) x 256 (tokens) block tile, 8 waves in a 2 x 4 grid (wave
+// tile 128 x 64 = 4 x 2 MFMA tiles, 128 int32 accumulators per lane), K consumed in stages of 64.
 //
-// LDS layout of one operand tile: 256 rows x 128 bytes; the eight 16-byte chunks of row r are
-// permuted by chunk ^ ((r >> 1) & 7), which spreads the sixteen rows a ds_read_b128 touches per
-// pass over all banks.  A direct-to-LDS load writes lane i's 16 bytes at base + 16 * i, so the
+// Staging.  Both operand tiles go global -> LDS with direct-to-LDS loads (no register staging)
+// into a ring of four 32 KB stages, so three stages (96 KB per CU) are in flight while one is
+// consumed; the loaded memory latency here is one to two microseconds and a stage lasts about
+// half a microsecond.  A stage's four loads per wave are issued one at a time between MFMA pairs.
+//
+// LDS layout of one operand stage: 256 rows x 64 bytes; the four 16-byte chunks of row r are
+// permuted by chunk ^ ((r >> 2) & 3), which spreads the sixteen rows one ds_read_b128 pass touches
+// over all 64 banks.  A direct-to-LDS load writes lane i's 16 bytes at base + 16 i, so the
 // permutation is applied on the global side: the lane that fills physical chunk pc of row r
-// fetches logical chunk pc ^ ((r >> 1) & 7).
+// fetches logical chunk pc ^ ((r >> 2) & 3).
+//
+// Synchronisation.  One barrier per stage, placed between the two k-steps: by then every wave
+// holds the stage's last operands in registers, so the stage can be refilled, and the operands of
+// the next stage's first k-step are fetched under the second k-step's MFMAs.  Operand reads and
+// their waits are inline asm; the wait counts below are exact (LDS reads and vector-memory loads
+// return in order).
+//
+// Epilogue.  Accumulators are dequantized in registers, staged as bf16 through the wave's own
+// 16 KB of the (now idle) ring with a 16-byte XOR swizzle, and written as full 256-byte row
+// segments with 16-byte stores.  Per-channel constants come from a 3 KB LDS table filled at kernel
+// start.
 //
 // Rows past the end of either matrix are clamped to the last valid row: their products land in
-// accumulators that are never stored.
+// accumulators that are never stored.  Workgroups are dealt round-robin to the 8 XCDs (each with
+// its own L2); the 32 workgroups one XCD runs together are mapped to a compact patch of tiles.
 // ------------------------------------------------------------------------------------------------
 constexpr int kTile = 256;
-constexpr int kBK = 128;
+constexpr int kBK = 64;
+constexpr int kStages = 4;
 constexpr int kPrefillThreads = 512;
-constexpr int kStageBytes = kTile * kBK;   // one operand, one stage: 32 KB
+constexpr int kOpBytes = kTile * kBK;        // one operand, one stage: 16 KB
+constexpr int kStageBytes = 2 * kOpBytes;    // W then X: 32 KB
+constexpr int kRingBytes = kStages * kStageBytes;
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
-__device__ __forceinline__ void load_tile_to_lds(const int8_t* const (&src)[4], int k0, int8_t* stage, int wave) {
+// ---- LDS operand reads and waits as inline asm: the compiler's wait-count pass then sees no LDS
+// read that could alias the in-flight direct-to-LDS loads, and the waits below are the only ones.
+template <int OFF>
+__device__ __forceinline__ v4i lds_read16(unsigned addr) {
+    v4i v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+__device__ __forceinline__ void read_ops(unsigned addrA, unsigned addrB, v4i (&a)[4], v4i (&b)[2]) {
+    a[0] = lds_read16<0 * 32 * kBK>(addrA);
+    a[1] = lds_read16<1 * 32 * kBK>(addrA);
+    a[2] = lds_read16<2 * 32 * kBK>(addrA);
+    a[3] = lds_read16<3 * 32 * kBK>(addrA);
+    b[0] = lds_read16<0 * 32 * kBK>(addrB);
+    b[1] = lds_read16<1 * 32 * kBK>(addrB);
+}
+// waits until at most N LDS reads are outstanding; the operands are tied to the wait so that no
+// MFMA that consumes them can be scheduled above it
+template <int N>
+__device__ __forceinline__ void wait_ops(v4i (&a)[4], v4i (&b)[2]) {
+    asm volatile("s_waitcnt lgkmcnt(%6)"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1])
+                 : "n"(N));
+}
+__device__ __forceinline__ void mfma_block(const v4i (&a)[4], const v4i (&b)[2], v16i (&acc)[4][2]) {
 #pragma unroll
-    for (int pss = 0; pss < 4; ++pss) {
-        int8_t* dst = stage + (pss * 64 + wave * 8) * kBK;     // wave-uniform; lane i lands at dst + 16 i
-        __builtin_amdgcn_global_load_lds((global_void*)(src[pss] + k0), (lds_void*)dst, 16, 0, 0);
-    }
-    // keep the prefetch where it is written: ahead of the MFMA work that hides its latency
-    __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
-__device__ __forceinline__ void compute_stage(const int8_t* sW, const int8_t* sX, const int (&offA)[4],
-                                              const int (&offB)[4], v16i (&acc)[4][2]) {
+
+__device__ __forceinline__ void load_stage(const int8_t* const (&srcW)[2], const int8_t* const (&srcX)[2], int k0,
+                                            int8_t* stage, int wave) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        v4i a[4], b[2];
+    for (int pss = 0; pss < 2; ++pss)
+        __builtin_amdgcn_global_load_lds((global_void*)(srcW[pss] + k0), (lds_void*)(stage + (pss * 128 + wave * 16) * kBK), 16, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const v4i*>(sW + offA[ks] + i * 32 * kBK);
+    for (int pss = 0; pss < 2; ++pss)
+        __builtin_amdgcn_global_load_lds((global_void*)(srcX[pss] + k0), (lds_void*)(stage + kOpBytes + (pss * 128 + wave * 16) * kBK), 16, 0, 0);
+}
+
+// One K stage (two MFMA k-steps).  The four direct-to-LDS loads of stage s+4 are issued one at a
+// time between pairs of MFMAs, so that no wave sits in a full address queue with its MFMAs unissued.
+template <bool TAIL>
+__device__ __forceinline__ void stage_step(int s, int nk, int8_t* smem, unsigned lds_base, const int8_t* const (&srcW)[2],
+                                           const int8_t* const (&srcX)[2], const unsigned (&offA)[2], const unsigned (&offB)[2],
+                                           int wave, v4i (&a0)[4], v4i (&b0)[2], v4i (&a1)[4], v4i (&b1)[2], v16i (&acc)[4][2]) {
+    const unsigned cur = lds_base + (s & 3) * kStageBytes;
+    const unsigned nxt = lds_base + ((s + 1) & 3) * kStageBytes;
+    read_ops(cur + offA[1], cur + kOpBytes + offB[1], a1, b1);
+    wait_ops<6>(a0, b0);
+    mfma_block(a0, b0, acc);
+    __builtin_amdgcn_sched_barrier(0);   // the MFMAs above cover the latency of the reads waited for below
+    if (TAIL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    wait_ops<0>(a1, b1);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    read_ops(nxt + offA[0], nxt + kOpBytes + offB[0], a0, b0);
+    const bool do_load = s + kStages < nk;
+    int8_t* dst = smem + (s & 3) * kStageBytes;
+    const int k0 = (s + kStages) * kBK;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const v4i*>(sX + offB[ks] + j * 32 * kBK);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < 4; ++i) {
+        if (do_load) {
+            const int8_t* src = (i < 2 ? srcW[i] : srcX[i - 2]) + k0;
+            int8_t* d = dst + (i < 2 ? 0 : kOpBytes) + ((i & 1) * 128 + wave * 16) * kBK;
+            __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)d, 16, 0, 0);
+        }
+        acc[i][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[0], acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[1], acc[i][1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-__global__ __launch_bounds__(kPrefillThreads) void linear_prefill_kernel(LinearArgs p, int tiles_o, int n_blocks) {
-    __shared__ __attribute__((aligned(1024))) int8_t sW0[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) int8_t sW1[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) int8_t sX0[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) int8_t sX1[kStageBytes];
+__global__ __launch_bounds__(kPrefillThreads) void linear_prefill_kernel(LinearArgs p, int tiles_m, int tiles_o, int patch_o, int patch_m) {
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+    __shared__ __attribute__((aligned(16))) float c_dw[kTile];
+    __shared__ __attribute__((aligned(16))) int c_ws[kTile];
+    __shared__ __attribute__((aligned(16))) float c_bias[kTile];
+    const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>(smem));
 
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them so
-    // that one XCD works on consecutive tiles (same token rows, neighbouring weight columns).
+    // XCD-aware 2-D patches: the 32 workgroups an XCD runs together form a patch_m x patch_o patch
     const int bid = blockIdx.x;
-    const int xcd = bid & 7, per = n_blocks >> 3, rem = n_blocks & 7;
-    const int logical = xcd * per + min(xcd, rem) + (bid >> 3);
-    const int tile_m = logical / tiles_o, tile_o = logical - tile_m * tiles_o;
+    const int xcd = bid & 7, j = bid >> 3;
+    const int patch = (j >> 5) * 8 + xcd, idx = j & 31;
+    const int npo = (tiles_o + patch_o - 1) / patch_o;
+    const int po = patch % npo, pm = patch / npo;
+    const int tile_o = po * patch_o + idx % patch_o;
+    const int tile_m = pm * patch_m + idx / patch_o;
+    if (tile_o >= tiles_o || tile_m >= tiles_m) return;
     const long long m0 = static_cast<long long>(tile_m) * kTile;
     const int o0 = tile_o * kTile;
 
@@ -169,24 +240,21 @@ __global__ __launch_bounds__(kPrefillThreads) void linear_prefill_kernel(LinearA
     const int l32 = lane & 31, hi = lane >> 5;
     const int wo = wave & 1, wm = wave >> 1;
 
-    // global sources of this lane's four 16-byte pieces per operand
-    const int8_t* srcW[4];
-    const int8_t* srcX[4];
+    const int8_t* srcW[2];
+    const int8_t* srcX[2];
 #pragma unroll
-    for (int pss = 0; pss < 4; ++pss) {
-        const int r = pss * 64 + wave * 8 + (lane >> 3);
-        const int lc = (lane & 7) ^ ((r >> 1) & 7);
+    for (int pss = 0; pss < 2; ++pss) {
+        const int r = pss * 128 + wave * 16 + (lane >> 2);
+        const int lc = (lane & 3) ^ ((r >> 2) & 3);
         const int ro = min(o0 + r, p.N - 1);
         const long long rm = min(m0 + r, static_cast<long long>(p.M) - 1);
         srcW[pss] = p.wq + static_cast<size_t>(ro) * p.K + lc * 16;
         srcX[pss] = p.q + static_cast<size_t>(rm) * p.K + lc * 16;
     }
-
-    // LDS byte offsets of this lane's MFMA operands for the four K steps of a stage
-    int offA[4], offB[4];
-    const int swz = (l32 >> 1) & 7;
+    unsigned offA[2], offB[2];
+    const int swz = (l32 >> 2) & 3;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < 2; ++ks) {
         const int pc = ((ks * 2 + hi) ^ swz) * 16;
         offA[ks] = (wo * 128 + l32) * kBK + pc;
         offB[ks] = (wm * 64 + l32) * kBK + pc;
@@ -196,54 +264,107 @@ __global__ __launch_bounds__(kPrefillThreads) void linear_prefill_kernel(LinearA
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = (v16i){0};
+        for (int jj = 0; jj < 2; ++jj) acc[i][jj] = (v16i){0};
 
+    {   // per-output-channel constants of this tile, read back in the epilogue
+        const int o = min(o0 + (tid & 255), p.N - 1);
+        if (tid < 256) { c_dw[tid] = p.dw[o]; c_ws[tid] = p.wsum[o]; }
+        else c_bias[tid - 256] = p.bias ? p.bias[o] : 0.0f;
+    }
     const int nk = p.K / kBK;
-    load_tile_to_lds(srcW, 0, sW0, wave);
-    load_tile_to_lds(srcX, 0, sX0, wave);
-    int it = 0;
-    for (; it + 2 <= nk; it += 2) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        load_tile_to_lds(srcW, (it + 1) * kBK, sW1, wave);
-        load_tile_to_lds(srcX, (it + 1) * kBK, sX1, wave);
-        compute_stage(sW0, sX0, offA, offB, acc);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (it + 2 < nk) {
-            load_tile_to_lds(srcW, (it + 2) * kBK, sW0, wave);
-            load_tile_to_lds(srcX, (it + 2) * kBK, sX0, wave);
+    // prologue: up to four stages in flight
+#pragma unroll
+    for (int s = 0; s < kStages; ++s)
+        if (s < nk) load_stage(srcW, srcX, s * kBK, smem + s * kStageBytes, wave);
+    if (nk >= 4) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    v4i a0[4], b0[2], a1[4], b1[2];
+    read_ops(lds_base + offA[0], lds_base + kOpBytes + offB[0], a0, b0);
+
+    int s = 0;
+    const int n_steady = nk - 3;
+    for (; s < n_steady; ++s) stage_step<false>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
+    for (; s < nk; ++s) stage_step<true>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
+    wait_ops<0>(a0, b0);   // the last prefetch read stale data; drain it
+
+    if (p.acc_dbg) {   // raw accumulators for the bit-exact check (debug path, not tuned)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const long long m = m0 + wm * 64 + jj * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int o4 = o0 + wo * 128 + i * 32 + 8 * g + 4 * hi;
+                    if (m < p.M && o4 < p.N)
+                        *reinterpret_cast<int4*>(p.acc_dbg + m * p.N + o4) =
+                            make_int4(acc[i][jj][4 * g], acc[i][jj][4 * g + 1], acc[i][jj][4 * g + 2], acc[i][jj][4 * g + 3]);
+                }
         }
-        compute_stage(sW1, sX1, offA, offB, acc);
-    }
-    if (it < nk) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        compute_stage(sW0, sX0, offA, offB, acc);
     }
 
-    // epilogue
+    // ---- epilogue: dequantize, stage bf16 through this wave's 16 KB of LDS, store full rows ----
+    __syncthreads();   // every wave is done reading operands; also orders the constants written at the start
+    int8_t* stage = smem + wave * 16384;
+    float dt[2];
+    int zs[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const long long m = m0 + wm * 64 + j * 32 + l32;
-        if (m >= p.M) continue;
-        const int t = static_cast<int>(m % p.L);
-        const float dt = p.delta[t];
-        const int zs = p.zp[t] - p.off;
+    for (int jj = 0; jj < 2; ++jj) {
+        int m = static_cast<int>(m0) + wm * 64 + jj * 32 + l32;
+        if (m >= p.M) m = p.M - 1;
+        const int t = m % p.L;
+        dt[jj] = p.delta[t];
+        zs[jj] = p.zp[t] - p.off;
+    }
+    float4 dwv = *reinterpret_cast<const float4*>(c_dw + wo * 128 + 4 * hi);
+    int4 wsv = *reinterpret_cast<const int4*>(c_ws + wo * 128 + 4 * hi);
+    float4 bv = *reinterpret_cast<const float4*>(c_bias + wo * 128 + 4 * hi);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int o4 = o0 + wo * 128 + i * 32 + 8 * g + 4 * hi;
-                if (o4 >= p.N) continue;
-                const float4 dwv = *reinterpret_cast<const float4*>(p.dw + o4);
-                const int4 wsv = *reinterpret_cast<const int4*>(p.wsum + o4);
-                float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (p.bias) bv = *reinterpret_cast<const float4*>(p.bias + o4);
-                epilogue_store4(p, m, o4, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
-                                acc[i][j][4 * g + 3], dt, zs, dwv, wsv, bv);
-            }
+    for (int c = 0; c < 16; ++c) {           // c = i * 4 + g: output channels wo*128 + 8c + 4hi .. +3
+        float4 dwn = dwv, bn = bv;
+        int4 wsn = wsv;
+        if (c < 15) {
+            const int ol = wo * 128 + 8 * (c + 1) + 4 * hi;
+            dwn = *reinterpret_cast<const float4*>(c_dw + ol);
+            wsn = *reinterpret_cast<const int4*>(c_ws + ol);
+            bn = *reinterpret_cast<const float4*>(c_bias + ol);
         }
+        const int i = c >> 2, g = c & 3;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int row = jj * 32 + l32;
+            const float y0 = fmaf(static_cast<float>(acc[i][jj][4 * g] - __mul24(zs[jj], wsv.x)), dt[jj] * dwv.x, bv.x);
+            const float y1 = fmaf(static_cast<float>(acc[i][jj][4 * g + 1] - __mul24(zs[jj], wsv.y)), dt[jj] * dwv.y, bv.y);
+            const float y2 = fmaf(static_cast<float>(acc[i][jj][4 * g + 2] - __mul24(zs[jj], wsv.z)), dt[jj] * dwv.z, bv.z);
+            const float y3 = fmaf(static_cast<float>(acc[i][jj][4 * g + 3] - __mul24(zs[jj], wsv.w)), dt[jj] * dwv.w, bv.w);
+            uint2 out;
+            out.x = pack_bf16(y0, y1);
+            out.y = pack_bf16(y2, y3);
+            *reinterpret_cast<uint2*>(stage + row * 256 + ((c ^ (row & 15)) * 16) + hi * 8) = out;
+        }
+        dwv = dwn; wsv = wsn; bv = bn;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // same wave wrote and reads: LDS operations of one wave complete in order
+    const int cc = lane & 15;
+    const int o = o0 + wo * 128 + cc * 8;
+#pragma unroll
+    for (int r0 = 0; r0 < 16; r0 += 4) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = (r0 + u) * 4 + (lane >> 4);
+            v[u] = *reinterpret_cast<const uint4*>(stage + row * 256 + ((cc ^ (row & 15)) * 16));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = (r0 + u) * 4 + (lane >> 4);
+            const long long m = m0 + wm * 64 + row;
+            if (m < p.M && o < p.N) *reinterpret_cast<uint4*>(p.y + m * p.N + o) = v[u];
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -273,11 +394,20 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
     if (schedule == STWQ_SCHEDULE_AUTO) schedule = (tiled_ok && M >= 256) ? STWQ_SCHEDULE_PREFILL : STWQ_SCHEDULE_GENERIC;
     if (schedule == STWQ_SCHEDULE_PREFILL) {
         if (!tiled_ok) return fail(STWQ_EUNSUPPORTED, "stwq_linear: the prefill schedule needs K %% %d == 0 (K = %d)", kBK, p.K);
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_prefill_kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
+        if (attr != hipSuccess) return fail(STWQ_EHIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr));
         const int tiles_o = (p.N + kTile - 1) / kTile;
-        const long long n_blocks = ((M + kTile - 1) / kTile) * tiles_o;
+        const long long tiles_m = (M + kTile - 1) / kTile;
+        // patch of tiles one XCD works on at a time: patch_o x patch_m = 32
+        int patch_o = tiles_o < 4 ? tiles_o : 4;
+        while (32 % patch_o) --patch_o;
+        const int patch_m = 32 / patch_o;
+        const long long n_patches = ((tiles_o + patch_o - 1) / patch_o) * ((tiles_m + patch_m - 1) / patch_m);
+        const long long n_blocks = ((n_patches + 7) / 8) * 8 * 32;
         STWQ_REQUIRE(n_blocks <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
-        linear_prefill_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(kPrefillThreads), 0, s>>>(
-            p, tiles_o, static_cast<int>(n_blocks));
+        linear_prefill_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(kPrefillThreads), kRingBytes, s>>>(
+            p, static_cast<int>(tiles_m), tiles_o, patch_o, patch_m);
         return launch_status("linear_prefill_kernel");
     }
     if (schedule == STWQ_SCHEDULE_GENERIC) {

@@ -51,8 +51,8 @@ def test_invalid_arguments_return_einval_without_a_gpu():
     assert l.stwq_linear(p, 4, 1 << 17, 16, 2, p, p, p, p, p, 8, None, p, None, None) == EINVAL     # K too large
     assert l.stwq_linear(p, 4, 32, 16, 2, p, p, p, p, p, 8, None, None, None, None) == EINVAL
     assert l.stwq_linear_ex(p, 4, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 99, None) == EINVAL   # schedule
-    assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 2, None) == -2      # prefill needs K % 128
-    assert b"128" in l.stwq_last_error()
+    assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 2, None) == -2      # prefill needs K % 64
+    assert b"64" in l.stwq_last_error()
 
 
 def test_finalize_host_helper():
