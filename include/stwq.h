@@ -25,6 +25,7 @@
 #ifndef STWQ_H
 #define STWQ_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -69,6 +70,26 @@ STWQ_API int stwq_calibrate_stats(const float* x_dev, int64_t rows, int L, int C
  * All arrays are host arrays of length L. */
 STWQ_API int stwq_finalize_act_params(const float* pos_min, const float* pos_max, int L, int a_bits,
                              float* delta, float* inv_delta, int32_t* zp);
+
+/* Gain-Projected Scaling: the closed-form per-input-channel scale s (Section 4.1 Step 4 and the
+ * appendix "Algorithm of GPS") from calibration activations and the unscaled weights.
+ *   Q(X): Eq. 1 with one (delta, z) for the whole tensor (a_bits, min-max, range widened to hold 0);
+ *   Q(W): symmetric per output channel (w_bits);  dX = X - Q(X), dW = W - Q(W);
+ *   k = argmax_i R_x[i] (lowest index on ties);  s_k = sqrt(R_x[k] / R_w[k]);
+ *   s_i = s_k sqrt((sum_o |dW[o,i]|)(sum_r |x[r,i]|)) / sqrt((sum_o |W[o,i]|)(sum_r |dx[r,i]|)),
+ *   s_i = 1 where either product is zero; s is clamped to [1e-5, 1e5].
+ *   range_mode 0: R = 2 absmax for both R_x[i] and R_w[k] (range of column k of w_dev over all
+ *   rows); range_mode 1: R = max - min.
+ *   x_dev [rows, K] fp32 (16-byte aligned, K a multiple of 4); w_dev [N, K] fp32;
+ *   ch_min_dev, ch_max_dev, ch_absmax_dev [K]: statistics of x_dev from stwq_calibrate_stats;
+ *   work_dev: scratch of gps_workspace_bytes(N, K) bytes, 16-byte aligned, contents ignored on
+ *   entry and undefined on return;  s_dev [K] fp32 output.
+ * Sums are fp64 and accumulated with atomics: s can differ in its last bits between runs. */
+STWQ_API size_t gps_workspace_bytes(int N, int K);
+STWQ_API int gps_solve_scale(const float* x_dev, int64_t rows, int K, const float* w_dev, int N,
+                             int a_bits, int w_bits, int range_mode,
+                             const float* ch_min_dev, const float* ch_max_dev, const float* ch_absmax_dev,
+                             void* work_dev, float* s_dev, void* stream);
 
 /* Equivalent scaling folded into the weights (Eq. 2) and per-output-channel symmetric weight
  * quantization:

@@ -19,7 +19,7 @@ _lib = None
 SCHEDULE_AUTO, SCHEDULE_GENERIC, SCHEDULE_PREFILL, SCHEDULE_DECODE = 0, 1, 2, 3
 
 EXPORTS = ("stwq_last_error", "stwq_version", "stwq_calibrate_stats", "stwq_finalize_act_params",
-           "gps_fold_weights", "stwq_quantize_act", "stwq_linear", "stwq_linear_ex")
+           "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_linear", "stwq_linear_ex")
 
 
 class StwqError(RuntimeError):
@@ -50,6 +50,10 @@ def lib() -> C.CDLL:
     l.stwq_calibrate_stats.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     l.stwq_finalize_act_params.restype = i32
     l.stwq_finalize_act_params.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    l.gps_workspace_bytes.restype = C.c_size_t
+    l.gps_workspace_bytes.argtypes = [i32, i32]
+    l.gps_solve_scale.restype = i32
+    l.gps_solve_scale.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     l.gps_fold_weights.restype = i32
     l.gps_fold_weights.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     l.stwq_quantize_act.restype = i32
@@ -120,6 +124,24 @@ def stwq_finalize_act_params(pos_min: np.ndarray, pos_max: np.ndarray, a_bits: i
     _check(lib().stwq_finalize_act_params(pmin.ctypes.data, pmax.ctypes.data, L, a_bits,
                                           delta.ctypes.data, inv_delta.ctypes.data, zp.ctypes.data))
     return delta, inv_delta, zp
+
+
+def gps_workspace_bytes(N: int, K: int) -> int:
+    return int(lib().gps_workspace_bytes(N, K))
+
+
+def gps_solve_scale(x, w, a_bits: int, w_bits: int, ch_min, ch_max, ch_absmax, work, s, range_mode: int = 0) -> None:
+    """GPS scale into s [K]; work is a uint8 device tensor of at least gps_workspace_bytes(N, K) bytes."""
+    import torch
+    rows, K = x.shape
+    N = w.shape[0]
+    if work.dtype != torch.uint8 or not work.is_cuda or work.numel() < gps_workspace_bytes(N, K):
+        raise ValueError("work must be a uint8 device tensor of at least gps_workspace_bytes(N, K) bytes")
+    _check(lib().gps_solve_scale(
+        _dev(x, torch.float32, None, "x"), rows, K, _dev(w, torch.float32, (N, K), "w"), N, a_bits, w_bits, range_mode,
+        _dev(ch_min, torch.float32, (K,), "ch_min"), _dev(ch_max, torch.float32, (K,), "ch_max"),
+        _dev(ch_absmax, torch.float32, (K,), "ch_absmax"), work.data_ptr(), _dev(s, torch.float32, (K,), "s"),
+        _stream(x)))
 
 
 def gps_fold_weights(w, s, w_bits: int, wq, dw, wsum, inv_s=None) -> None:

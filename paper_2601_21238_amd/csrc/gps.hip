@@ -1,0 +1,267 @@
+// Gain-Projected Scaling: the closed-form per-input-channel scale (Section 4.1 Step 4; appendix
+// "Algorithm of GPS").
+//
+//   1. X_q = Q(X) per tensor (Eq. 1, b_a bits, min-max), W_q = Q(W) per output channel (symmetric,
+//      b_w bits); dX = X - X_q, dW = W - W_q.
+//   2. R_x[i] = range of activation channel i; k = argmax R_x.
+//   3. s_k = sqrt(R_x[k] / R_w[k]), R_w[k] the range of input-channel k of W over the outputs.
+//   4. s_i = s_k sqrt(sum_j |dW_ij x_i|) / sqrt(sum_j |W_ij dx_i|), summed over calibration rows;
+//      the double sum factorises into (sum_j |dW_ij|)(sum_r |x_ri|) and (sum_j |W_ij|)(sum_r |dx_ri|).
+//
+// Two HBM-bound passes (4 B per activation, 4 B per weight read twice) reduce X and W to five
+// vectors of length K in fp64; one small kernel evaluates the closed form.  fp64 sums are
+// accumulated with atomics, so the last bits of s may differ from run to run (the scale is a
+// heuristic, compared at 1e-5 relative).
+#include "common.h"
+
+namespace stwq {
+
+constexpr int kGpsThreads = 256;
+constexpr int kGpsSlab = kGpsThreads * 4;
+constexpr int kGpsRows = 32;           // weight rows per block in the column-sum pass
+
+// Workspace layout (doubles first for alignment).
+struct GpsWork {
+    double* sum_abs_x;    // [K]
+    double* sum_abs_dx;   // [K]
+    double* sum_abs_w;    // [K]
+    double* sum_abs_dw;   // [K]
+    double* qparams;      // [4]: delta, 1/delta, z, unused
+    float* w_min;         // [K]
+    float* w_max;         // [K]
+    float* w_absmax;      // [K]
+    float* row_absmax;    // [N]
+};
+
+static size_t gps_work_bytes(int N, int K) {
+    return sizeof(double) * (4 * static_cast<size_t>(K) + 4) + sizeof(float) * (3 * static_cast<size_t>(K) + N);
+}
+
+static GpsWork carve(void* base, int N, int K) {
+    GpsWork w;
+    double* d = static_cast<double*>(base);
+    w.sum_abs_x = d;
+    w.sum_abs_dx = d + K;
+    w.sum_abs_w = d + 2 * static_cast<size_t>(K);
+    w.sum_abs_dw = d + 3 * static_cast<size_t>(K);
+    w.qparams = d + 4 * static_cast<size_t>(K);
+    float* f = reinterpret_cast<float*>(w.qparams + 4);
+    w.w_min = f;
+    w.w_max = f + K;
+    w.w_absmax = f + 2 * static_cast<size_t>(K);
+    w.row_absmax = f + 3 * static_cast<size_t>(K);
+    return w;
+}
+
+// Clears the accumulators; block 0 also reduces the channel statistics to the per-tensor
+// quantizer of step 1 (range widened to contain zero).
+__global__ __launch_bounds__(kGpsThreads) void gps_init_kernel(GpsWork w, int K, const float* __restrict__ ch_min,
+                                                               const float* __restrict__ ch_max, double qmax) {
+    const int tid = threadIdx.x;
+    for (int k = blockIdx.x * kGpsThreads + tid; k < K; k += gridDim.x * kGpsThreads) {
+        w.sum_abs_x[k] = 0.0;
+        w.sum_abs_dx[k] = 0.0;
+        w.sum_abs_w[k] = 0.0;
+        w.sum_abs_dw[k] = 0.0;
+        w.w_min[k] = __builtin_inff();
+        w.w_max[k] = -__builtin_inff();
+        w.w_absmax[k] = 0.0f;
+    }
+    if (blockIdx.x != 0) return;
+    __shared__ float red_lo[kGpsThreads / 64], red_hi[kGpsThreads / 64];
+    float lo = 0.0f, hi = 0.0f;
+    for (int k = tid; k < K; k += kGpsThreads) {
+        lo = fminf(lo, ch_min[k]);
+        hi = fmaxf(hi, ch_max[k]);
+    }
+    lo = wave_min(lo);
+    hi = wave_max(hi);
+    if ((tid & 63) == 0) { red_lo[tid >> 6] = lo; red_hi[tid >> 6] = hi; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int i = 1; i < kGpsThreads / 64; ++i) { lo = fminf(lo, red_lo[i]); hi = fmaxf(hi, red_hi[i]); }
+        const double range = fmax(static_cast<double>(hi) - static_cast<double>(lo), 1e-30);
+        const double delta = range / qmax;
+        w.qparams[0] = delta;
+        w.qparams[1] = 1.0 / delta;
+        w.qparams[2] = rint(-static_cast<double>(lo) / delta);
+        w.qparams[3] = 0.0;
+    }
+}
+
+// Pass over the calibration activations: per channel sum |x| and sum |x - Q(x)|.
+__global__ __launch_bounds__(kGpsThreads) void gps_x_kernel(const float* __restrict__ x, long long rows, int K, GpsWork w,
+                                                            double qmax, long long rows_per_block) {
+    const int c0 = blockIdx.y * kGpsSlab + threadIdx.x * 4;
+    if (c0 >= K) return;
+    const double delta = w.qparams[0], inv_delta = w.qparams[1], z = w.qparams[2];
+    const long long r0 = blockIdx.x * rows_per_block;
+    const long long r1 = min(r0 + rows_per_block, rows);
+    double sx[4] = {0, 0, 0, 0}, sdx[4] = {0, 0, 0, 0};
+    for (long long r = r0; r < r1; ++r) {
+        const float4 v = *reinterpret_cast<const float4*>(x + r * K + c0);
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double xd = static_cast<double>(e[j]);
+            const double code = fmin(fmax(rint(xd * inv_delta) + z, 0.0), qmax);
+            sx[j] += fabs(xd);
+            sdx[j] += fabs(xd - delta * (code - z));
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        atomicAdd(w.sum_abs_x + c0 + j, sx[j]);
+        atomicAdd(w.sum_abs_dx + c0 + j, sdx[j]);
+    }
+}
+
+// Per output row absmax of the unscaled weights.
+__global__ __launch_bounds__(kGpsThreads) void gps_w_rowmax_kernel(const float* __restrict__ wt, int K, GpsWork w) {
+    __shared__ float red[kGpsThreads / 64];
+    const int tid = threadIdx.x, o = blockIdx.x;
+    const float4* row = reinterpret_cast<const float4*>(wt + static_cast<size_t>(o) * K);
+    float amax = 0.0f;
+    for (int k4 = tid; k4 < (K >> 2); k4 += kGpsThreads) {
+        const float4 v = row[k4];
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    amax = wave_max(amax);
+    if ((tid & 63) == 0) red[tid >> 6] = amax;
+    __syncthreads();
+    if (tid == 0) {
+        for (int i = 1; i < kGpsThreads / 64; ++i) amax = fmaxf(amax, red[i]);
+        w.row_absmax[o] = amax;
+    }
+}
+
+// Column sums over output rows: per input channel sum |W|, sum |W - Q(W)| and the channel's range.
+__global__ __launch_bounds__(kGpsThreads) void gps_w_kernel(const float* __restrict__ wt, int N, int K, GpsWork w, double qw) {
+    const int c0 = blockIdx.y * kGpsSlab + threadIdx.x * 4;
+    if (c0 >= K) return;
+    const int o0 = blockIdx.x * kGpsRows, o1 = min(o0 + kGpsRows, N);
+    double sw[4] = {0, 0, 0, 0}, sdw[4] = {0, 0, 0, 0};
+    float mn[4], mx[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { mn[j] = __builtin_inff(); mx[j] = -__builtin_inff(); }
+    for (int o = o0; o < o1; ++o) {
+        const float amax = w.row_absmax[o];
+        const double dw = amax > 0.0f ? static_cast<double>(amax) / qw : 1.0;
+        const float4 v = *reinterpret_cast<const float4*>(wt + static_cast<size_t>(o) * K + c0);
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double wd = static_cast<double>(e[j]);
+            const double code = fmin(fmax(rint(wd / dw), -(qw + 1.0)), qw);
+            sw[j] += fabs(wd);
+            sdw[j] += fabs(wd - dw * code);
+            mn[j] = fminf(mn[j], e[j]);
+            mx[j] = fmaxf(mx[j], e[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        atomicAdd(w.sum_abs_w + c0 + j, sw[j]);
+        atomicAdd(w.sum_abs_dw + c0 + j, sdw[j]);
+        atomic_min_f32(w.w_min + c0 + j, mn[j]);
+        atomic_max_f32(w.w_max + c0 + j, mx[j]);
+        atomic_max_f32(w.w_absmax + c0 + j, fmaxf(fabsf(mn[j]), fabsf(mx[j])));
+    }
+}
+
+// Steps 2-4: anchor channel (largest activation range, lowest index on ties), s_k, closed form.
+__global__ __launch_bounds__(1024) void gps_finalize_kernel(GpsWork w, int K, int range_mode, const float* __restrict__ ch_min,
+                                                            const float* __restrict__ ch_max, const float* __restrict__ ch_absmax,
+                                                            float* __restrict__ s_out) {
+    __shared__ double best_r[16];
+    __shared__ int best_k[16];
+    __shared__ double s_anchor;
+    __shared__ int k_anchor;
+    const int tid = threadIdx.x;
+    double r_best = -1.0;
+    int k_best = 0x7FFFFFFF;
+    for (int k = tid; k < K; k += 1024) {
+        const double r = range_mode == 1 ? static_cast<double>(ch_max[k]) - static_cast<double>(ch_min[k])
+                                         : 2.0 * static_cast<double>(ch_absmax[k]);
+        if (r > r_best) { r_best = r; k_best = k; }     // ascending k per thread: first maximum kept
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double r2 = __shfl_xor(r_best, off, 64);
+        const int k2 = __shfl_xor(k_best, off, 64);
+        if (r2 > r_best || (r2 == r_best && k2 < k_best)) { r_best = r2; k_best = k2; }
+    }
+    if ((tid & 63) == 0) { best_r[tid >> 6] = r_best; best_k[tid >> 6] = k_best; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int i = 1; i < 16; ++i)
+            if (best_r[i] > r_best || (best_r[i] == r_best && best_k[i] < k_best)) { r_best = best_r[i]; k_best = best_k[i]; }
+        const double r_w = range_mode == 1 ? static_cast<double>(w.w_max[k_best]) - static_cast<double>(w.w_min[k_best])
+                                           : 2.0 * static_cast<double>(w.w_absmax[k_best]);
+        s_anchor = (r_best > 0.0 && r_w > 0.0) ? sqrt(r_best / r_w) : 1.0;
+        k_anchor = k_best;
+    }
+    __syncthreads();
+    const double sk = s_anchor;
+    for (int k = tid; k < K; k += 1024) {
+        const double num = w.sum_abs_dw[k] * w.sum_abs_x[k];
+        const double den = w.sum_abs_w[k] * w.sum_abs_dx[k];
+        double s = (num > 0.0 && den > 0.0) ? sk * sqrt(num) / sqrt(den) : 1.0;
+        if (k == k_anchor) s = sk;
+        s_out[k] = static_cast<float>(fmin(fmax(s, 1e-5), 1e5));
+    }
+}
+
+}  // namespace stwq
+
+extern "C" size_t gps_workspace_bytes(int N, int K) {
+    if (N <= 0 || K <= 0) return 0;
+    return stwq::gps_work_bytes(N, K);
+}
+
+extern "C" int gps_solve_scale(const float* x_dev, int64_t rows, int K, const float* w_dev, int N,
+                               int a_bits, int w_bits, int range_mode,
+                               const float* ch_min_dev, const float* ch_max_dev, const float* ch_absmax_dev,
+                               void* work_dev, float* s_dev, void* stream) {
+    using namespace stwq;
+    clear_error();
+    STWQ_REQUIRE(x_dev && w_dev && ch_min_dev && ch_max_dev && ch_absmax_dev && work_dev && s_dev,
+                 "gps_solve_scale: null pointer");
+    STWQ_REQUIRE(rows > 0 && K > 0 && N > 0, "gps_solve_scale: rows = %lld, K = %d, N = %d must be positive",
+                 static_cast<long long>(rows), K, N);
+    STWQ_REQUIRE(K % 4 == 0, "gps_solve_scale: K = %d must be a multiple of 4", K);
+    STWQ_REQUIRE((a_bits == 8 || a_bits == 6) && (w_bits == 8 || w_bits == 6),
+                 "gps_solve_scale: a_bits = %d, w_bits = %d, expected 6 or 8", a_bits, w_bits);
+    STWQ_REQUIRE(range_mode == 0 || range_mode == 1, "gps_solve_scale: range_mode = %d, expected 0 (absmax) or 1 (minmax)",
+                 range_mode);
+    STWQ_REQUIRE(aligned16(x_dev) && aligned16(w_dev) && aligned16(work_dev),
+                 "gps_solve_scale: x_dev, w_dev and work_dev must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const GpsWork w = carve(work_dev, N, K);
+    const double qmax = static_cast<double>((1 << a_bits) - 1);
+    const double qw = static_cast<double>((1 << (w_bits - 1)) - 1);
+    const int slabs = (K + kGpsSlab - 1) / kGpsSlab;
+
+    gps_init_kernel<<<dim3((K + kGpsThreads - 1) / kGpsThreads), dim3(kGpsThreads), 0, s>>>(w, K, ch_min_dev, ch_max_dev, qmax);
+    int rc = launch_status("gps_init_kernel");
+    if (rc != STWQ_OK) return rc;
+
+    long long gx = 2048 / slabs;                       // about eight blocks per CU
+    if (gx < 1) gx = 1;
+    if (gx > rows) gx = rows;
+    const long long rows_per_block = (rows + gx - 1) / gx;
+    gx = (rows + rows_per_block - 1) / rows_per_block;
+    gps_x_kernel<<<dim3(static_cast<unsigned>(gx), slabs), dim3(kGpsThreads), 0, s>>>(x_dev, rows, K, w, qmax, rows_per_block);
+    rc = launch_status("gps_x_kernel");
+    if (rc != STWQ_OK) return rc;
+
+    gps_w_rowmax_kernel<<<dim3(N), dim3(kGpsThreads), 0, s>>>(w_dev, K, w);
+    rc = launch_status("gps_w_rowmax_kernel");
+    if (rc != STWQ_OK) return rc;
+    gps_w_kernel<<<dim3((N + kGpsRows - 1) / kGpsRows, slabs), dim3(kGpsThreads), 0, s>>>(w_dev, N, K, w, qw);
+    rc = launch_status("gps_w_kernel");
+    if (rc != STWQ_OK) return rc;
+
+    gps_finalize_kernel<<<dim3(1), dim3(1024), 0, s>>>(w, K, range_mode, ch_min_dev, ch_max_dev, ch_absmax_dev, s_dev);
+    return launch_status("gps_finalize_kernel");
+}

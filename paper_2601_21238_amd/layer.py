@@ -22,6 +22,7 @@ class StwqLinear:
         self.wq = torch.empty((N, K), dtype=torch.int8, device=d)
         self.dw = torch.empty(N, dtype=torch.float32, device=d)
         self.wsum = torch.empty(N, dtype=torch.int32, device=d)
+        self.s: Optional[torch.Tensor] = None
         self.inv_s: Optional[torch.Tensor] = None
         self.bias: Optional[torch.Tensor] = None
         self.pos_min = torch.full((L,), float("inf"), dtype=torch.float32, device=d)
@@ -40,10 +41,19 @@ class StwqLinear:
         B.stwq_calibrate_stats(x_calib, self.L, ch_min=ch_min, ch_max=ch_max, ch_absmax=ch_abs)
         return ch_min, ch_max, ch_abs
 
+    def solve_scale(self, x_calib: torch.Tensor, w: torch.Tensor, range_mode: int = 0) -> torch.Tensor:
+        """GPS scale (Section 4.1) from calibration activations and the unscaled weights."""
+        ch_min, ch_max, ch_abs = self.channel_stats(x_calib)
+        work = torch.empty(B.gps_workspace_bytes(self.N, self.K), dtype=torch.uint8, device=self.device)
+        s = torch.empty(self.K, dtype=torch.float32, device=self.device)
+        B.gps_solve_scale(x_calib, w, self.a_bits, self.w_bits, ch_min, ch_max, ch_abs, work, s, range_mode)
+        return s
+
     def fold(self, w: torch.Tensor, s: Optional[torch.Tensor], bias: Optional[torch.Tensor]) -> None:
         """Eq. 2 folding and weight quantization; keeps 1/s for the activation side."""
         self.inv_s = torch.empty(self.K, dtype=torch.float32, device=self.device) if s is not None else None
         B.gps_fold_weights(w, s, self.w_bits, self.wq, self.dw, self.wsum, self.inv_s)
+        self.s = s
         self.bias = bias
 
     def accumulate_position_stats(self, x_calib: torch.Tensor) -> None:

@@ -163,3 +163,23 @@ def test_edge_inputs(bits):
     # a single row
     G.check_forward(layer, pack, xt[:1], SCHEDULES["generic"], what="one row")
     G.check_forward(layer, pack, xt[:1], P.SCHEDULE_AUTO, what="one row/auto")
+
+
+# ---------------------------------------------------------------- GPS scale
+
+@pytest.mark.parametrize("K,N,L,n,bits,mode", [(64, 48, 8, 16, 8, 0), (1028, 72, 37, 9, 6, 1), (1024, 1024, 680, 8, 8, 0)])
+def test_gps_scale_matches_oracle(K, N, L, n, bits, mode):
+    spec = small_spec(K=K, N=N, L=L, batch=1, n_calib=n, a_bits=bits, w_bits=bits, n_outliers=min(8, K // 8))
+    w, _ = wl.make_weights(spec)
+    xc = wl.make_calibration(spec)
+    if K == 64:
+        xc[:, 5] = 0          # dead channel -> s = 1
+        w[:, 9] = 0           # zero weight column -> s = 1
+    s_ref = O.gps_scale(xc, w, bits, bits, "absmax" if mode == 0 else "minmax")
+    layer = StwqLinear(N, K, L, bits, bits, G.DEV)
+    s = layer.solve_scale(G.dev(xc), G.dev(w), range_mode=mode)
+    torch.cuda.synchronize()
+    got = G.host(s)
+    assert np.allclose(got, s_ref, rtol=1e-5, atol=0), np.abs(got / s_ref - 1).max()
+    if K == 64:
+        assert got[5] == 1 and got[9] == 1
