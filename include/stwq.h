@@ -131,8 +131,9 @@ STWQ_API int stwq_linear(const int8_t* q_dev, int64_t M, int K, int N, int L,
  * results; the integer part is bit-identical across schedules):
  *   STWQ_SCHEDULE_AUTO     what stwq_linear does;
  *   STWQ_SCHEDULE_GENERIC  one wave per 32 x 32 tile straight from global memory, any valid shape;
- *   STWQ_SCHEDULE_PREFILL  256 x 256 LDS-staged MFMA tiles, needs K a multiple of 64;
- *   STWQ_SCHEDULE_DECODE   weight-streaming tiles for M <= 256, needs K a multiple of 64.
+ *   STWQ_SCHEDULE_PREFILL  256 x 256 LDS-staged MFMA tiles (MFMA-bound shapes), K a multiple of 64;
+ *   STWQ_SCHEDULE_DECODE   128 x 128 tiles over an eight-stage ring (weight-streaming shapes, small M),
+ *                          K a multiple of 64.
  * A schedule that cannot take the shape returns STWQ_EUNSUPPORTED. */
 #define STWQ_SCHEDULE_AUTO    0
 #define STWQ_SCHEDULE_GENERIC 1
@@ -143,6 +144,30 @@ STWQ_API int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,
                    const float* delta_dev, const int32_t* zp_dev, int a_bits,
                    const float* bias_dev,
                    uint16_t* y_bf16_dev, int32_t* acc_dbg_dev, int schedule, void* stream);
+
+/* One problem of a grouped launch: the arguments of stwq_linear, all pointers DEVICE pointers. */
+typedef struct stwq_linear_problem {
+    const int8_t*  q_dev;
+    const int8_t*  wq_dev;
+    const float*   dw_dev;
+    const int32_t* wsum_dev;
+    const float*   delta_dev;
+    const int32_t* zp_dev;
+    const float*   bias_dev;      /* may be NULL */
+    uint16_t*      y_bf16_dev;
+    int32_t*       acc_dbg_dev;   /* may be NULL */
+    int32_t        M, K, N, L, a_bits, reserved;
+} stwq_linear_problem;
+
+/* Grouped form of stwq_linear for steps made of many small independent linears (an autoregressive
+ * decode step streams every layer's weights once against about a hundred rows): all problems run
+ * in ONE launch with the DECODE schedule, so that launch latency does not hide the weight stream.
+ *   problems      HOST array of count descriptors (read during the call only: validation and grid size);
+ *   problems_dev  DEVICE copy of the same count descriptors, made by the caller, 8-byte aligned; the
+ *                 kernel reads it, so it must stay unchanged until the stream has passed this call.
+ * Every problem must satisfy stwq_linear's rules and have K a multiple of 64; 1 <= count <= 4096. */
+STWQ_API int stwq_linear_grouped(const stwq_linear_problem* problems, int count,
+                                 const stwq_linear_problem* problems_dev, void* stream);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,15 @@ _lib = None
 SCHEDULE_AUTO, SCHEDULE_GENERIC, SCHEDULE_PREFILL, SCHEDULE_DECODE = 0, 1, 2, 3
 
 EXPORTS = ("stwq_last_error", "stwq_version", "stwq_calibrate_stats", "stwq_finalize_act_params",
-           "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_linear", "stwq_linear_ex")
+           "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_linear", "stwq_linear_ex", "stwq_linear_grouped")
+
+
+class LinearProblem(C.Structure):
+    """Mirror of stwq_linear_problem."""
+    _fields_ = [("q_dev", C.c_void_p), ("wq_dev", C.c_void_p), ("dw_dev", C.c_void_p), ("wsum_dev", C.c_void_p),
+                ("delta_dev", C.c_void_p), ("zp_dev", C.c_void_p), ("bias_dev", C.c_void_p), ("y_bf16_dev", C.c_void_p),
+                ("acc_dbg_dev", C.c_void_p), ("M", C.c_int32), ("K", C.c_int32), ("N", C.c_int32), ("L", C.c_int32),
+                ("a_bits", C.c_int32), ("reserved", C.c_int32)]
 
 
 class StwqError(RuntimeError):
@@ -62,6 +70,8 @@ def lib() -> C.CDLL:
     l.stwq_linear.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     l.stwq_linear_ex.restype = i32
     l.stwq_linear_ex.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
+    l.stwq_linear_grouped.restype = i32
+    l.stwq_linear_grouped.argtypes = [vp, i32, vp, vp]
     _lib = l
     return l
 
@@ -173,3 +183,41 @@ def stwq_linear(q, wq, dw, wsum, delta, zp, a_bits: int, bias, y, L: int, acc_db
         _dev(delta, torch.float32, (L,), "delta"), _dev(zp, torch.int32, (L,), "zp"), a_bits,
         _dev(bias, torch.float32, (N,), "bias", True), _dev(y, torch.bfloat16, (M, N), "y"),
         _dev(acc_dbg, torch.int32, (M, N), "acc_dbg", True), schedule, _stream(q)))
+
+
+class LinearGroup:
+    """A fixed list of linear problems prepared once for stwq_linear_grouped (descriptors on host and device)."""
+
+    def __init__(self, problems):
+        """problems: list of dicts with the keyword arguments of stwq_linear (q, wq, dw, wsum, delta, zp, a_bits,
+        bias, y, L, and optionally acc_dbg).  The tensors must stay alive as long as the group is used."""
+        import torch
+        self.count = len(problems)
+        self.host = (LinearProblem * self.count)()
+        self._keep = problems
+        dev = None
+        for i, pr in enumerate(problems):
+            q, wq = pr["q"], pr["wq"]
+            M, K = q.shape
+            N = wq.shape[0]
+            L = pr["L"]
+            h = self.host[i]
+            h.q_dev = _dev(q, torch.int8, None, "q")
+            h.wq_dev = _dev(wq, torch.int8, (N, K), "wq")
+            h.dw_dev = _dev(pr["dw"], torch.float32, (N,), "dw")
+            h.wsum_dev = _dev(pr["wsum"], torch.int32, (N,), "wsum")
+            h.delta_dev = _dev(pr["delta"], torch.float32, (L,), "delta")
+            h.zp_dev = _dev(pr["zp"], torch.int32, (L,), "zp")
+            h.bias_dev = _dev(pr.get("bias"), torch.float32, (N,), "bias", True)
+            h.y_bf16_dev = _dev(pr["y"], torch.bfloat16, (M, N), "y")
+            h.acc_dbg_dev = _dev(pr.get("acc_dbg"), torch.int32, (M, N), "acc_dbg", True)
+            h.M, h.K, h.N, h.L, h.a_bits, h.reserved = M, K, N, L, pr["a_bits"], 0
+            dev = q.device
+        raw = np.frombuffer(bytes(self.host), dtype=np.uint8).copy()
+        self.dev = torch.from_numpy(raw).to(dev)
+        self.device = dev
+
+    def run(self) -> None:
+        import torch
+        _check(lib().stwq_linear_grouped(C.addressof(self.host), self.count, self.dev.data_ptr(),
+                                         torch.cuda.current_stream(self.device).cuda_stream))

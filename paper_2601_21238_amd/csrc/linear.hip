@@ -10,12 +10,15 @@
 // runs of four consecutive output channels, which are contiguous in the row-major [M, N] output.
 // Inside one MFMA both operands take the same 16-byte K chunk per lane, and integer sums commute,
 // so any consistent assignment of K chunks to lanes gives the exact result.
+#include <utility>
+
 #include "common.h"
 
 namespace stwq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
@@ -101,130 +104,329 @@ __global__ __launch_bounds__(kSimpleThreads) void linear_simple_kernel(LinearArg
 }
 
 // ------------------------------------------------------------------------------------------------
-// Prefill kernel: 256 (output channels) x 256 (tokens) block tile, 8 waves in a 2 x 4 grid (wave
-// tile 128 x 64 = 4 x 2 MFMA tiles, 128 int32 accumulators per lane), K consumed in stages of 64.
+// Tiled kernel.  A workgroup of WO x WM waves computes a (WO TI 32) x (WM TJ 32) tile of
+// output channels x tokens; each wave owns TI x TJ MFMA tiles.  K is consumed in stages of 64.
 //
-// Staging.  Both operand tiles go global -> LDS with direct-to-LDS loads (no register staging)
-// into a ring of four 32 KB stages, so three stages (96 KB per CU) are in flight while one is
-// consumed; the loaded memory latency here is one to two microseconds and a stage lasts about
-// half a microsecond.  A stage's four loads per wave are issued one at a time between MFMA pairs.
+//   prefill: 2 x 4 waves, 4 x 2 MFMA tiles per wave -> 256 x 256 tile, 128 accumulators per lane,
+//            ring of four 32 KB stages (three in flight, 96 KB per CU);
+//   decode : 2 x 2 waves, 2 x 2 MFMA tiles per wave -> 128 x 128 tile (all rows of a decode step
+//            against 128 output channels), ring of eight 16 KB stages (seven in flight, 112 KB per
+//            CU): the weight stream is the bottleneck and only bytes in flight hide HBM latency.
 //
-// LDS layout of one operand stage: 256 rows x 64 bytes; the four 16-byte chunks of row r are
-// permuted by chunk ^ ((r >> 2) & 3), which spreads the sixteen rows one ds_read_b128 pass touches
-// over all 64 banks.  A direct-to-LDS load writes lane i's 16 bytes at base + 16 i, so the
-// permutation is applied on the global side: the lane that fills physical chunk pc of row r
-// fetches logical chunk pc ^ ((r >> 2) & 3).
+// Staging.  Both operand tiles go global -> LDS with direct-to-LDS loads (no register staging).
+// The loaded memory latency here is one to two microseconds and a prefill stage lasts about half
+// a microsecond, hence the deep rings.  A stage's loads are issued between MFMA groups.
+//
+// LDS layout of one operand stage: rows x 64 bytes; the four 16-byte chunks of row r are permuted
+// by chunk ^ ((r >> 2) & 3), which spreads the sixteen rows one ds_read_b128 pass touches over all
+// 64 banks.  A direct-to-LDS load writes lane i's 16 bytes at base + 16 i, so the permutation is
+// applied on the global side: the lane that fills physical chunk pc of row r fetches logical
+// chunk pc ^ ((r >> 2) & 3).
 //
 // Synchronisation.  One barrier per stage, placed between the two k-steps: by then every wave
 // holds the stage's last operands in registers, so the stage can be refilled, and the operands of
 // the next stage's first k-step are fetched under the second k-step's MFMAs.  Operand reads and
-// their waits are inline asm; the wait counts below are exact (LDS reads and vector-memory loads
-// return in order).
+// their waits are inline asm: the compiler's wait-count pass then sees no LDS read that could
+// alias the in-flight direct-to-LDS loads, and the waits written here are the only ones.  The
+// counts are exact because LDS reads and vector-memory loads each return in issue order.
 //
 // Epilogue.  Accumulators are dequantized in registers, staged as bf16 through the wave's own
-// 16 KB of the (now idle) ring with a 16-byte XOR swizzle, and written as full 256-byte row
-// segments with 16-byte stores.  Per-channel constants come from a 3 KB LDS table filled at kernel
-// start.
+// slice of the (now idle) ring with a 16-byte XOR swizzle, and written as full row segments with
+// 16-byte stores.  Per-channel constants come from a small LDS table filled at kernel start.
 //
 // Rows past the end of either matrix are clamped to the last valid row: their products land in
-// accumulators that are never stored.  Workgroups are dealt round-robin to the 8 XCDs (each with
-// its own L2); the 32 workgroups one XCD runs together are mapped to a compact patch of tiles.
+// accumulators that are never stored.
 // ------------------------------------------------------------------------------------------------
-constexpr int kTile = 256;
 constexpr int kBK = 64;
-constexpr int kStages = 4;
-constexpr int kPrefillThreads = 512;
-constexpr int kOpBytes = kTile * kBK;        // one operand, one stage: 16 KB
-constexpr int kStageBytes = 2 * kOpBytes;    // W then X: 32 KB
-constexpr int kRingBytes = kStages * kStageBytes;
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
-// ---- LDS operand reads and waits as inline asm: the compiler's wait-count pass then sees no LDS
-// read that could alias the in-flight direct-to-LDS loads, and the waits below are the only ones.
+template <int WO_, int WM_, int TI_, int TJ_, int STAGES_>
+struct TileCfg {
+    static constexpr int WO = WO_, WM = WM_, TI = TI_, TJ = TJ_, STAGES = STAGES_;
+    static constexpr int kWaves = WO * WM;
+    static constexpr int kThreads = kWaves * 64;
+    static constexpr int kTileO = WO * TI * 32;
+    static constexpr int kTileM = WM * TJ * 32;
+    static constexpr int kOpW = kTileO * kBK;             // bytes of the weight tile per stage
+    static constexpr int kOpX = kTileM * kBK;
+    static constexpr int kStage = kOpW + kOpX;
+    static constexpr int kRing = STAGES * kStage;
+    static constexpr int kLoadsW = kTileO / 16 / kWaves;  // direct-to-LDS loads per wave and stage (16 rows each)
+    static constexpr int kLoadsX = kTileM / 16 / kWaves;
+    static constexpr int kLoads = kLoadsW + kLoadsX;
+    static constexpr int kChunks = TI * 4;                // 16-byte bf16 chunks per staged output row
+    static constexpr int kWaveOut = TJ * 32 * TI * 64;    // bytes of one wave's staged output
+    static_assert((STAGES & (STAGES - 1)) == 0 && STAGES >= 2, "ring size must be a power of two");
+    static_assert(kTileO % (16 * kWaves) == 0 && kTileM % (16 * kWaves) == 0, "tile rows must split over the waves");
+    static_assert(kWaves * kWaveOut <= kRing, "output staging must fit the ring");
+    static_assert(kLoads * (STAGES - 1) <= 63, "vmcnt is a 6-bit counter");
+};
+typedef TileCfg<2, 4, 4, 2, 4> PrefillCfg;
+typedef TileCfg<2, 2, 2, 2, 8> DecodeCfg;
+
 template <int OFF>
 __device__ __forceinline__ v4i lds_read16(unsigned addr) {
     v4i v;
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
     return v;
 }
-__device__ __forceinline__ void read_ops(unsigned addrA, unsigned addrB, v4i (&a)[4], v4i (&b)[2]) {
-    a[0] = lds_read16<0 * 32 * kBK>(addrA);
-    a[1] = lds_read16<1 * 32 * kBK>(addrA);
-    a[2] = lds_read16<2 * 32 * kBK>(addrA);
-    a[3] = lds_read16<3 * 32 * kBK>(addrA);
-    b[0] = lds_read16<0 * 32 * kBK>(addrB);
-    b[1] = lds_read16<1 * 32 * kBK>(addrB);
+template <int T, int... I>
+__device__ __forceinline__ void read_rows(unsigned addr, v4i (&r)[T], std::integer_sequence<int, I...>) {
+    ((r[I] = lds_read16<I * 32 * kBK>(addr)), ...);
 }
-// waits until at most N LDS reads are outstanding; the operands are tied to the wait so that no
-// MFMA that consumes them can be scheduled above it
+template <int TI, int TJ>
+__device__ __forceinline__ void read_ops(unsigned addrA, unsigned addrB, v4i (&a)[TI], v4i (&b)[TJ]) {
+    read_rows(addrA, a, std::make_integer_sequence<int, TI>{});
+    read_rows(addrB, b, std::make_integer_sequence<int, TJ>{});
+}
+// Waits until at most N LDS reads are outstanding.  The operands pass through the asm statements so
+// that no MFMA that consumes them can be scheduled above the wait.
+template <int N, int TI, int TJ>
+__device__ __forceinline__ void wait_ops(v4i (&a)[TI], v4i (&b)[TJ]) {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+#pragma unroll
+    for (int i = 0; i < TI; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) asm volatile("" : "+v"(b[j]));
+}
 template <int N>
-__device__ __forceinline__ void wait_ops(v4i (&a)[4], v4i (&b)[2]) {
-    asm volatile("s_waitcnt lgkmcnt(%6)"
-                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1])
-                 : "n"(N));
-}
-__device__ __forceinline__ void mfma_block(const v4i (&a)[4], const v4i (&b)[2], v16i (&acc)[4][2]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+__device__ __forceinline__ void wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-
-__device__ __forceinline__ void load_stage(const int8_t* const (&srcW)[2], const int8_t* const (&srcX)[2], int k0,
-                                            int8_t* stage, int wave) {
-#pragma unroll
-    for (int pss = 0; pss < 2; ++pss)
-        __builtin_amdgcn_global_load_lds((global_void*)(srcW[pss] + k0), (lds_void*)(stage + (pss * 128 + wave * 16) * kBK), 16, 0, 0);
-#pragma unroll
-    for (int pss = 0; pss < 2; ++pss)
-        __builtin_amdgcn_global_load_lds((global_void*)(srcX[pss] + k0), (lds_void*)(stage + kOpBytes + (pss * 128 + wave * 16) * kBK), 16, 0, 0);
+// The l-th direct-to-LDS load of this wave for one stage: weight rows first, then token rows.
+template <class C>
+__device__ __forceinline__ void issue_load(int l, const int8_t* const (&srcW)[C::kLoadsW], const int8_t* const (&srcX)[C::kLoadsX],
+                                           int k0, int8_t* stage, int wave) {
+    if (l < C::kLoadsW) {
+        int8_t* dst = stage + (l * C::kWaves * 16 + wave * 16) * kBK;     // wave-uniform; lane i lands at dst + 16 i
+        __builtin_amdgcn_global_load_lds((global_void*)(srcW[l] + k0), (lds_void*)dst, 16, 0, 0);
+    } else {
+        const int u = l - C::kLoadsW;
+        int8_t* dst = stage + C::kOpW + (u * C::kWaves * 16 + wave * 16) * kBK;
+        __builtin_amdgcn_global_load_lds((global_void*)(srcX[u] + k0), (lds_void*)dst, 16, 0, 0);
+    }
 }
 
-// One K stage (two MFMA k-steps).  The four direct-to-LDS loads of stage s+4 are issued one at a
-// time between pairs of MFMAs, so that no wave sits in a full address queue with its MFMAs unissued.
-template <bool TAIL>
-__device__ __forceinline__ void stage_step(int s, int nk, int8_t* smem, unsigned lds_base, const int8_t* const (&srcW)[2],
-                                           const int8_t* const (&srcX)[2], const unsigned (&offA)[2], const unsigned (&offB)[2],
-                                           int wave, v4i (&a0)[4], v4i (&b0)[2], v4i (&a1)[4], v4i (&b1)[2], v16i (&acc)[4][2]) {
-    const unsigned cur = lds_base + (s & 3) * kStageBytes;
-    const unsigned nxt = lds_base + ((s + 1) & 3) * kStageBytes;
-    read_ops(cur + offA[1], cur + kOpBytes + offB[1], a1, b1);
-    wait_ops<6>(a0, b0);
-    mfma_block(a0, b0, acc);
+// One K stage (two MFMA k-steps).
+template <class C, bool TAIL>
+__device__ __forceinline__ void stage_step(int s, int nk, int8_t* smem, unsigned lds_base,
+                                           const int8_t* const (&srcW)[C::kLoadsW], const int8_t* const (&srcX)[C::kLoadsX],
+                                           const unsigned (&offA)[2], const unsigned (&offB)[2], int wave,
+                                           v4i (&a0)[C::TI], v4i (&b0)[C::TJ], v4i (&a1)[C::TI], v4i (&b1)[C::TJ],
+                                           v16i (&acc)[C::TI][C::TJ]) {
+    constexpr int TI = C::TI, TJ = C::TJ;
+    const unsigned cur = lds_base + (s & (C::STAGES - 1)) * C::kStage;
+    const unsigned nxt = lds_base + ((s + 1) & (C::STAGES - 1)) * C::kStage;
+    read_ops<TI, TJ>(cur + offA[1], cur + C::kOpW + offB[1], a1, b1);
+    wait_ops<TI + TJ, TI, TJ>(a0, b0);
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);   // the MFMAs above cover the latency of the reads waited for below
-    if (TAIL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    wait_ops<0>(a1, b1);
+    // stage s+1 must have landed; in the steady state the STAGES-2 younger stages may still be in flight
+    if (TAIL) wait_vm<0>();
+    else wait_vm<C::kLoads * (C::STAGES - 2)>();
+    wait_ops<0, TI, TJ>(a1, b1);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    read_ops(nxt + offA[0], nxt + kOpBytes + offB[0], a0, b0);
-    const bool do_load = s + kStages < nk;
-    int8_t* dst = smem + (s & 3) * kStageBytes;
-    const int k0 = (s + kStages) * kBK;
+    read_ops<TI, TJ>(nxt + offA[0], nxt + C::kOpW + offB[0], a0, b0);
+    // refill the stage every wave has just finished reading, one load per MFMA group
+    const bool do_load = s + C::STAGES < nk;
+    int8_t* dst = smem + (s & (C::STAGES - 1)) * C::kStage;
+    const int k0 = (s + C::STAGES) * kBK;
+    constexpr int per_slot = (C::kLoads + TI - 1) / TI;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < TI; ++i) {
         if (do_load) {
-            const int8_t* src = (i < 2 ? srcW[i] : srcX[i - 2]) + k0;
-            int8_t* d = dst + (i < 2 ? 0 : kOpBytes) + ((i & 1) * 128 + wave * 16) * kBK;
-            __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)d, 16, 0, 0);
+#pragma unroll
+            for (int l = i * per_slot; l < (i + 1) * per_slot && l < C::kLoads; ++l) issue_load<C>(l, srcW, srcX, k0, dst, wave);
         }
-        acc[i][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[0], acc[i][0], 0, 0, 0);
-        acc[i][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[1], acc[i][1], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-__global__ __launch_bounds__(kPrefillThreads) void linear_prefill_kernel(LinearArgs p, int tiles_m, int tiles_o, int patch_o, int patch_m) {
-    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
-    __shared__ __attribute__((aligned(16))) float c_dw[kTile];
-    __shared__ __attribute__((aligned(16))) int c_ws[kTile];
-    __shared__ __attribute__((aligned(16))) float c_bias[kTile];
+// Computes one output tile of problem p: rows m0.. of tokens, channels o0.. .
+template <class C>
+__device__ __forceinline__ void compute_tile(const LinearArgs& p, long long m0, int o0, int8_t* smem,
+                                             float* c_dw, int* c_ws, float* c_bias) {
+    constexpr int TI = C::TI, TJ = C::TJ;
     const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>(smem));
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int wo = wave % C::WO, wm = wave / C::WO;
 
-    // XCD-aware 2-D patches: the 32 workgroups an XCD runs together form a patch_m x patch_o patch
+    // global sources of this lane's 16-byte pieces: lane i of a load fills row i/4, physical chunk i%4
+    const int8_t* srcW[C::kLoadsW];
+    const int8_t* srcX[C::kLoadsX];
+#pragma unroll
+    for (int u = 0; u < C::kLoadsW; ++u) {
+        const int r = u * C::kWaves * 16 + wave * 16 + (lane >> 2);
+        const int lc = (lane & 3) ^ ((r >> 2) & 3);
+        srcW[u] = p.wq + static_cast<size_t>(min(o0 + r, p.N - 1)) * p.K + lc * 16;
+    }
+#pragma unroll
+    for (int u = 0; u < C::kLoadsX; ++u) {
+        const int r = u * C::kWaves * 16 + wave * 16 + (lane >> 2);
+        const int lc = (lane & 3) ^ ((r >> 2) & 3);
+        srcX[u] = p.q + static_cast<size_t>(min(m0 + r, static_cast<long long>(p.M) - 1)) * p.K + lc * 16;
+    }
+    // LDS byte offsets of this lane's MFMA operands for the two k-steps of a stage
+    unsigned offA[2], offB[2];
+    const int swz = (l32 >> 2) & 3;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int pc = ((ks * 2 + hi) ^ swz) * 16;
+        offA[ks] = (wo * TI * 32 + l32) * kBK + pc;
+        offB[ks] = (wm * TJ * 32 + l32) * kBK + pc;
+    }
+
+    v16i acc[TI][TJ];
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) acc[i][j] = (v16i){0};
+
+    // per-output-channel constants of this tile, read back in the epilogue
+    for (int r = tid; r < C::kTileO; r += C::kThreads) {
+        const int o = min(o0 + r, p.N - 1);
+        c_dw[r] = p.dw[o];
+        c_ws[r] = p.wsum[o];
+        c_bias[r] = p.bias ? p.bias[o] : 0.0f;
+    }
+
+    const int nk = p.K / kBK;
+#pragma unroll
+    for (int s = 0; s < C::STAGES; ++s)
+        if (s < nk) {
+#pragma unroll
+            for (int l = 0; l < C::kLoads; ++l) issue_load<C>(l, srcW, srcX, s * kBK, smem + s * C::kStage, wave);
+        }
+    if (nk >= C::STAGES) wait_vm<C::kLoads * (C::STAGES - 1)>();
+    else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    v4i a0[TI], b0[TJ], a1[TI], b1[TJ];
+    read_ops<TI, TJ>(lds_base + offA[0], lds_base + C::kOpW + offB[0], a0, b0);
+
+    int s = 0;
+    const int n_steady = nk - (C::STAGES - 1);
+    for (; s < n_steady; ++s) stage_step<C, false>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
+    for (; s < nk; ++s) stage_step<C, true>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
+    wait_ops<0, TI, TJ>(a0, b0);   // the last prefetch read a stage nobody filled; drain it
+
+    if (p.acc_dbg) {   // raw accumulators for the bit-exact check (debug path, not tuned)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            const long long m = m0 + wm * TJ * 32 + j * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int o4 = o0 + wo * TI * 32 + i * 32 + 8 * g + 4 * hi;
+                    if (m < p.M && o4 < p.N)
+                        *reinterpret_cast<int4*>(p.acc_dbg + m * p.N + o4) =
+                            make_int4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                }
+        }
+    }
+
+    // ---- epilogue: dequantize, stage bf16 through this wave's slice of the ring, store full rows ----
+    __syncthreads();   // every wave is done reading operands; the constants table is complete
+    int8_t* stage = smem + wave * C::kWaveOut;
+    constexpr int kRowBytes = TI * 64;
+    float dt[TJ];
+    int zs[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+        int m = static_cast<int>(m0) + wm * TJ * 32 + j * 32 + l32;
+        if (m >= p.M) m = p.M - 1;
+        const int t = m % p.L;
+        dt[j] = p.delta[t];
+        zs[j] = p.zp[t] - p.off;
+    }
+    const int cbase = wo * TI * 32 + 4 * hi;
+    float4 dwv = *reinterpret_cast<const float4*>(c_dw + cbase);
+    int4 wsv = *reinterpret_cast<const int4*>(c_ws + cbase);
+    float4 bv = *reinterpret_cast<const float4*>(c_bias + cbase);
+#pragma unroll
+    for (int c = 0; c < C::kChunks; ++c) {       // c = 4 i + g: channels wo TI 32 + 8 c + 4 hi .. + 3
+        float4 dwn = dwv, bn = bv;
+        int4 wsn = wsv;
+        if (c + 1 < C::kChunks) {                // fetch the next group's constants under this group's arithmetic
+            dwn = *reinterpret_cast<const float4*>(c_dw + cbase + 8 * (c + 1));
+            wsn = *reinterpret_cast<const int4*>(c_ws + cbase + 8 * (c + 1));
+            bn = *reinterpret_cast<const float4*>(c_bias + cbase + 8 * (c + 1));
+        }
+        const int i = c >> 2, g = c & 3;
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            const int row = j * 32 + l32;
+            const float y0 = fmaf(static_cast<float>(acc[i][j][4 * g] - __mul24(zs[j], wsv.x)), dt[j] * dwv.x, bv.x);
+            const float y1 = fmaf(static_cast<float>(acc[i][j][4 * g + 1] - __mul24(zs[j], wsv.y)), dt[j] * dwv.y, bv.y);
+            const float y2 = fmaf(static_cast<float>(acc[i][j][4 * g + 2] - __mul24(zs[j], wsv.z)), dt[j] * dwv.z, bv.z);
+            const float y3 = fmaf(static_cast<float>(acc[i][j][4 * g + 3] - __mul24(zs[j], wsv.w)), dt[j] * dwv.w, bv.w);
+            uint2 out;
+            out.x = pack_bf16(y0, y1);
+            out.y = pack_bf16(y2, y3);
+            *reinterpret_cast<uint2*>(stage + row * kRowBytes + ((c ^ (row & (C::kChunks - 1))) * 16) + hi * 8) = out;
+        }
+        dwv = dwn; wsv = wsn; bv = bn;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // the same wave wrote and now reads: LDS operations of one wave complete in order
+    constexpr int kRowsPerPass = 64 / C::kChunks;
+    constexpr int kPasses = TJ * 32 / kRowsPerPass;
+    const int cc = lane % C::kChunks;
+    const int o = o0 + wo * TI * 32 + cc * 8;
+    typedef __attribute__((address_space(1))) u4 global_u4;
+    global_u4* ybase = (global_u4*)(p.y + (m0 + wm * TJ * 32 + lane / C::kChunks) * p.N + o);
+    const long long row_step = static_cast<long long>(kRowsPerPass) * p.N / 8;     // in 16-byte units
+    const int8_t* sbase = stage + (lane / C::kChunks) * kRowBytes;
+    const bool o_ok = o < p.N;
+#pragma unroll
+    for (int r0 = 0; r0 < kPasses; r0 += 4) {
+        u4 v0, v1, v2, v3;
+        {
+            const int row = (r0 + 0) * kRowsPerPass + lane / C::kChunks;
+            v0 = *reinterpret_cast<const u4*>(sbase + (r0 + 0) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
+        }
+        {
+            const int row = (r0 + 1) * kRowsPerPass + lane / C::kChunks;
+            v1 = *reinterpret_cast<const u4*>(sbase + (r0 + 1) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
+        }
+        {
+            const int row = (r0 + 2) * kRowsPerPass + lane / C::kChunks;
+            v2 = *reinterpret_cast<const u4*>(sbase + (r0 + 2) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
+        }
+        {
+            const int row = (r0 + 3) * kRowsPerPass + lane / C::kChunks;
+            v3 = *reinterpret_cast<const u4*>(sbase + (r0 + 3) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
+        }
+        const long long mrow = m0 + wm * TJ * 32 + r0 * kRowsPerPass + lane / C::kChunks;
+        if (o_ok && mrow < p.M) ybase[(r0 + 0) * row_step] = v0;
+        if (o_ok && mrow + kRowsPerPass < p.M) ybase[(r0 + 1) * row_step] = v1;
+        if (o_ok && mrow + 2 * kRowsPerPass < p.M) ybase[(r0 + 2) * row_step] = v2;
+        if (o_ok && mrow + 3 * kRowsPerPass < p.M) ybase[(r0 + 3) * row_step] = v3;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Prefill launch: one tile per workgroup.  Workgroups are dealt round-robin to the 8 XCDs (each with
+// its own L2); the 32 workgroups one XCD runs together are mapped to a compact patch_m x patch_o
+// patch of tiles so that they share operand rows in that L2.
+__global__ __launch_bounds__(PrefillCfg::kThreads) void linear_prefill_kernel(LinearArgs p, int tiles_m, int tiles_o, int patch_o,
+                                                                              int patch_m) {
+    typedef PrefillCfg C;
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+    __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
+    __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
+    __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
     const int bid = blockIdx.x;
     const int xcd = bid & 7, j = bid >> 3;
     const int patch = (j >> 5) * 8 + xcd, idx = j & 31;
@@ -233,139 +435,42 @@ __global__ __launch_bounds__(kPrefillThreads) void linear_prefill_kernel(LinearA
     const int tile_o = po * patch_o + idx % patch_o;
     const int tile_m = pm * patch_m + idx / patch_o;
     if (tile_o >= tiles_o || tile_m >= tiles_m) return;
-    const long long m0 = static_cast<long long>(tile_m) * kTile;
-    const int o0 = tile_o * kTile;
+    compute_tile<C>(p, static_cast<long long>(tile_m) * C::kTileM, tile_o * C::kTileO, smem, c_dw, c_ws, c_bias);
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hi = lane >> 5;
-    const int wo = wave & 1, wm = wave >> 1;
+__device__ __forceinline__ LinearArgs args_of(const stwq_linear_problem& q) {
+    LinearArgs p;
+    p.q = q.q_dev; p.wq = q.wq_dev; p.dw = q.dw_dev; p.wsum = q.wsum_dev; p.delta = q.delta_dev; p.zp = q.zp_dev;
+    p.bias = q.bias_dev; p.y = q.y_bf16_dev; p.acc_dbg = q.acc_dbg_dev;
+    p.M = q.M; p.K = q.K; p.N = q.N; p.L = q.L; p.off = q.a_bits == 8 ? 128 : 0;
+    return p;
+}
 
-    const int8_t* srcW[2];
-    const int8_t* srcX[2];
-#pragma unroll
-    for (int pss = 0; pss < 2; ++pss) {
-        const int r = pss * 128 + wave * 16 + (lane >> 2);
-        const int lc = (lane & 3) ^ ((r >> 2) & 3);
-        const int ro = min(o0 + r, p.N - 1);
-        const long long rm = min(m0 + r, static_cast<long long>(p.M) - 1);
-        srcW[pss] = p.wq + static_cast<size_t>(ro) * p.K + lc * 16;
-        srcX[pss] = p.q + static_cast<size_t>(rm) * p.K + lc * 16;
-    }
-    unsigned offA[2], offB[2];
-    const int swz = (l32 >> 2) & 3;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const int pc = ((ks * 2 + hi) ^ swz) * 16;
-        offA[ks] = (wo * 128 + l32) * kBK + pc;
-        offB[ks] = (wm * 64 + l32) * kBK + pc;
-    }
-
-    v16i acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) acc[i][jj] = (v16i){0};
-
-    {   // per-output-channel constants of this tile, read back in the epilogue
-        const int o = min(o0 + (tid & 255), p.N - 1);
-        if (tid < 256) { c_dw[tid] = p.dw[o]; c_ws[tid] = p.wsum[o]; }
-        else c_bias[tid - 256] = p.bias ? p.bias[o] : 0.0f;
-    }
-    const int nk = p.K / kBK;
-    // prologue: up to four stages in flight
-#pragma unroll
-    for (int s = 0; s < kStages; ++s)
-        if (s < nk) load_stage(srcW, srcX, s * kBK, smem + s * kStageBytes, wave);
-    if (nk >= 4) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    v4i a0[4], b0[2], a1[4], b1[2];
-    read_ops(lds_base + offA[0], lds_base + kOpBytes + offB[0], a0, b0);
-
-    int s = 0;
-    const int n_steady = nk - 3;
-    for (; s < n_steady; ++s) stage_step<false>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
-    for (; s < nk; ++s) stage_step<true>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
-    wait_ops<0>(a0, b0);   // the last prefetch read stale data; drain it
-
-    if (p.acc_dbg) {   // raw accumulators for the bit-exact check (debug path, not tuned)
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const long long m = m0 + wm * 64 + jj * 32 + l32;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int o4 = o0 + wo * 128 + i * 32 + 8 * g + 4 * hi;
-                    if (m < p.M && o4 < p.N)
-                        *reinterpret_cast<int4*>(p.acc_dbg + m * p.N + o4) =
-                            make_int4(acc[i][jj][4 * g], acc[i][jj][4 * g + 1], acc[i][jj][4 * g + 2], acc[i][jj][4 * g + 3]);
-                }
+// Decode launch, single problem or a group of problems in one launch: workgroup b takes tile b of
+// the concatenated tile lists (channel tiles fastest within a problem).
+__global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(LinearArgs single, const stwq_linear_problem* problems,
+                                                                            int count) {
+    typedef DecodeCfg C;
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+    __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
+    __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
+    __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
+    LinearArgs p = single;
+    int tile = blockIdx.x;
+    if (problems) {
+        int i = 0;
+        for (; i < count; ++i) {
+            const int tiles = ((problems[i].M + C::kTileM - 1) / C::kTileM) * ((problems[i].N + C::kTileO - 1) / C::kTileO);
+            if (tile < tiles) break;
+            tile -= tiles;
         }
+        if (i == count) return;
+        p = args_of(problems[i]);
     }
-
-    // ---- epilogue: dequantize, stage bf16 through this wave's 16 KB of LDS, store full rows ----
-    __syncthreads();   // every wave is done reading operands; also orders the constants written at the start
-    int8_t* stage = smem + wave * 16384;
-    float dt[2];
-    int zs[2];
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-        int m = static_cast<int>(m0) + wm * 64 + jj * 32 + l32;
-        if (m >= p.M) m = p.M - 1;
-        const int t = m % p.L;
-        dt[jj] = p.delta[t];
-        zs[jj] = p.zp[t] - p.off;
-    }
-    float4 dwv = *reinterpret_cast<const float4*>(c_dw + wo * 128 + 4 * hi);
-    int4 wsv = *reinterpret_cast<const int4*>(c_ws + wo * 128 + 4 * hi);
-    float4 bv = *reinterpret_cast<const float4*>(c_bias + wo * 128 + 4 * hi);
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {           // c = i * 4 + g: output channels wo*128 + 8c + 4hi .. +3
-        float4 dwn = dwv, bn = bv;
-        int4 wsn = wsv;
-        if (c < 15) {
-            const int ol = wo * 128 + 8 * (c + 1) + 4 * hi;
-            dwn = *reinterpret_cast<const float4*>(c_dw + ol);
-            wsn = *reinterpret_cast<const int4*>(c_ws + ol);
-            bn = *reinterpret_cast<const float4*>(c_bias + ol);
-        }
-        const int i = c >> 2, g = c & 3;
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int row = jj * 32 + l32;
-            const float y0 = fmaf(static_cast<float>(acc[i][jj][4 * g] - __mul24(zs[jj], wsv.x)), dt[jj] * dwv.x, bv.x);
-            const float y1 = fmaf(static_cast<float>(acc[i][jj][4 * g + 1] - __mul24(zs[jj], wsv.y)), dt[jj] * dwv.y, bv.y);
-            const float y2 = fmaf(static_cast<float>(acc[i][jj][4 * g + 2] - __mul24(zs[jj], wsv.z)), dt[jj] * dwv.z, bv.z);
-            const float y3 = fmaf(static_cast<float>(acc[i][jj][4 * g + 3] - __mul24(zs[jj], wsv.w)), dt[jj] * dwv.w, bv.w);
-            uint2 out;
-            out.x = pack_bf16(y0, y1);
-            out.y = pack_bf16(y2, y3);
-            *reinterpret_cast<uint2*>(stage + row * 256 + ((c ^ (row & 15)) * 16) + hi * 8) = out;
-        }
-        dwv = dwn; wsv = wsn; bv = bn;
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    // same wave wrote and reads: LDS operations of one wave complete in order
-    const int cc = lane & 15;
-    const int o = o0 + wo * 128 + cc * 8;
-#pragma unroll
-    for (int r0 = 0; r0 < 16; r0 += 4) {
-        uint4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int row = (r0 + u) * 4 + (lane >> 4);
-            v[u] = *reinterpret_cast<const uint4*>(stage + row * 256 + ((cc ^ (row & 15)) * 16));
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int row = (r0 + u) * 4 + (lane >> 4);
-            const long long m = m0 + wm * 64 + row;
-            if (m < p.M && o < p.N) *reinterpret_cast<uint4*>(p.y + m * p.N + o) = v[u];
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    const int tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
+    const int tile_m = tile / tiles_o, tile_o = tile - tile_m * tiles_o;
+    if (static_cast<long long>(tile_m) * C::kTileM >= p.M) return;
+    compute_tile<C>(p, static_cast<long long>(tile_m) * C::kTileM, tile_o * C::kTileO, smem, c_dw, c_ws, c_bias);
 }
 
 static int check_linear_args(const char* who, const int8_t* q, int64_t M, int K, int N, int L, const int8_t* wq,
@@ -387,18 +492,27 @@ static int check_linear_args(const char* who, const int8_t* q, int64_t M, int K,
 
 }  // namespace stwq
 
+template <class Kernel>
+static int set_ring(Kernel kernel, int bytes) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return stwq::fail(STWQ_EHIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
+    return STWQ_OK;
+}
+
 static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s) {
     using namespace stwq;
     const long long M = p.M;
     const bool tiled_ok = p.K % kBK == 0;
-    if (schedule == STWQ_SCHEDULE_AUTO) schedule = (tiled_ok && M >= 256) ? STWQ_SCHEDULE_PREFILL : STWQ_SCHEDULE_GENERIC;
+    if (schedule == STWQ_SCHEDULE_AUTO)
+        schedule = !tiled_ok ? STWQ_SCHEDULE_GENERIC : (M > 2 * DecodeCfg::kTileM ? STWQ_SCHEDULE_PREFILL : STWQ_SCHEDULE_DECODE);
+    if ((schedule == STWQ_SCHEDULE_PREFILL || schedule == STWQ_SCHEDULE_DECODE) && !tiled_ok)
+        return fail(STWQ_EUNSUPPORTED, "stwq_linear: the tiled schedules need K %% %d == 0 (K = %d)", kBK, p.K);
     if (schedule == STWQ_SCHEDULE_PREFILL) {
-        if (!tiled_ok) return fail(STWQ_EUNSUPPORTED, "stwq_linear: the prefill schedule needs K %% %d == 0 (K = %d)", kBK, p.K);
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_prefill_kernel),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
-        if (attr != hipSuccess) return fail(STWQ_EHIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr));
-        const int tiles_o = (p.N + kTile - 1) / kTile;
-        const long long tiles_m = (M + kTile - 1) / kTile;
+        typedef PrefillCfg C;
+        static const int attr = set_ring(linear_prefill_kernel, C::kRing);
+        if (attr != STWQ_OK) return attr;
+        const int tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
+        const long long tiles_m = (M + C::kTileM - 1) / C::kTileM;
         // patch of tiles one XCD works on at a time: patch_o x patch_m = 32
         int patch_o = tiles_o < 4 ? tiles_o : 4;
         while (32 % patch_o) --patch_o;
@@ -406,9 +520,18 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
         const long long n_patches = ((tiles_o + patch_o - 1) / patch_o) * ((tiles_m + patch_m - 1) / patch_m);
         const long long n_blocks = ((n_patches + 7) / 8) * 8 * 32;
         STWQ_REQUIRE(n_blocks <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
-        linear_prefill_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(kPrefillThreads), kRingBytes, s>>>(
+        linear_prefill_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(C::kThreads), C::kRing, s>>>(
             p, static_cast<int>(tiles_m), tiles_o, patch_o, patch_m);
         return launch_status("linear_prefill_kernel");
+    }
+    if (schedule == STWQ_SCHEDULE_DECODE) {
+        typedef DecodeCfg C;
+        static const int attr = set_ring(linear_decode_kernel, C::kRing);
+        if (attr != STWQ_OK) return attr;
+        const long long n_blocks = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
+        STWQ_REQUIRE(n_blocks <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
+        linear_decode_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(C::kThreads), C::kRing, s>>>(p, nullptr, 0);
+        return launch_status("linear_decode_kernel");
     }
     if (schedule == STWQ_SCHEDULE_GENERIC) {
         const long long gx = (M + 63) / 64;
@@ -418,6 +541,31 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
         return launch_status("linear_simple_kernel");
     }
     return fail(STWQ_EINVAL, "stwq_linear: unknown schedule %d", schedule);
+}
+
+extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int count,
+                                   const stwq_linear_problem* problems_dev, void* stream) {
+    using namespace stwq;
+    typedef DecodeCfg C;
+    clear_error();
+    STWQ_REQUIRE(problems && problems_dev, "stwq_linear_grouped: null pointer");
+    STWQ_REQUIRE(count > 0 && count <= 4096, "stwq_linear_grouped: count = %d must be in 1 .. 4096", count);
+    long long n_blocks = 0;
+    for (int i = 0; i < count; ++i) {
+        const stwq_linear_problem& q = problems[i];
+        const int rc = check_linear_args("stwq_linear_grouped", q.q_dev, q.M, q.K, q.N, q.L, q.wq_dev, q.dw_dev, q.wsum_dev,
+                                         q.delta_dev, q.zp_dev, q.a_bits, q.bias_dev, q.y_bf16_dev, q.acc_dbg_dev);
+        if (rc != STWQ_OK) return rc;
+        if (q.K % kBK != 0)
+            return fail(STWQ_EUNSUPPORTED, "stwq_linear_grouped: problem %d has K = %d, needs K %% %d == 0", i, q.K, kBK);
+        n_blocks += static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+    }
+    STWQ_REQUIRE(n_blocks <= 0x7FFFFFFFLL, "stwq_linear_grouped: too many tiles");
+    static const int attr = set_ring(linear_decode_kernel, C::kRing);
+    if (attr != STWQ_OK) return attr;
+    linear_decode_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(C::kThreads), C::kRing, static_cast<hipStream_t>(stream)>>>(
+        LinearArgs{}, problems_dev, count);
+    return launch_status("linear_decode_kernel (grouped)");
 }
 
 extern "C" int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,

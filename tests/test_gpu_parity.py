@@ -13,7 +13,7 @@ from paper_2601_21238_amd.layer import StwqLinear   # noqa: E402
 import gpu_common as G                       # noqa: E402
 
 F32 = np.float32
-SCHEDULES = {"generic": P.SCHEDULE_GENERIC, "prefill": P.SCHEDULE_PREFILL}
+SCHEDULES = {"generic": P.SCHEDULE_GENERIC, "prefill": P.SCHEDULE_PREFILL, "decode": P.SCHEDULE_DECODE}
 
 
 def small_spec(**kw):
@@ -98,9 +98,11 @@ CASES = [
     ("tiny",           16,   8,   3,  1,     4,     8,    ("generic",)),
     ("k_tail16",       144,  72,  37, 3,     6,     8,    ("generic",)),
     ("ragged_generic", 160,  200, 37, 5,     6,     6,    ("generic",)),
-    ("ragged_tiles",   256,  328, 131, 5,    6,     8,    ("generic", "prefill")),
-    ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "prefill")),
-    ("one_tile",       128,  256, 64, 4,     6,     8,    ("prefill",)),
+    ("ragged_tiles",   256,  328, 131, 5,    6,     8,    ("generic", "prefill", "decode")),
+    ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "prefill", "decode")),
+    ("one_tile",       128,  256, 64, 4,     6,     8,    ("prefill", "decode")),
+    ("one_stage",      64,   136, 9,  15,    6,     8,    ("prefill", "decode")),
+    ("long_k",         1280, 136, 30, 5,     6,     8,    ("prefill", "decode")),
 ]
 
 
@@ -117,8 +119,8 @@ def test_layer_small(case):
         G.check_forward(layer, pack, xt, SCHEDULES[sch], what=f"{name}/{sch}")
     # decode form: rows all at one position
     t0 = L // 2
-    G.check_forward(layer, pack, xt[t0::L][:1] if batch == 1 else xt[t0::L], SCHEDULES["generic"], t0=t0,
-                    what=f"{name}/decode-form")
+    for sch in {"generic", schedules[-1]}:
+        G.check_forward(layer, pack, xt[t0::L], SCHEDULES[sch], t0=t0, what=f"{name}/decode-form/{sch}")
 
 
 def test_config1_full():
@@ -129,12 +131,13 @@ def test_config1_full():
     layer = G.gpu_layer(spec, xc, w, b, pack["s"])
     G.check_calibration(layer, pack)
     results = {}
-    for sch in ("generic", "prefill"):
+    for sch in ("generic", "prefill", "decode"):
         results[sch] = G.check_forward(layer, pack, xt, SCHEDULES[sch], what=f"config1/{sch}")
     # run-to-run determinism and schedule independence of the integer part
     q2, acc2, y2 = G.check_forward(layer, pack, xt, SCHEDULES["prefill"], what="config1/prefill again")
     assert torch.equal(acc2, results["prefill"][1]) and torch.equal(y2, results["prefill"][2])
-    assert torch.equal(results["generic"][1], results["prefill"][1])
+    assert torch.equal(results["generic"][1], results["prefill"][1]) and torch.equal(results["decode"][1], results["prefill"][1])
+    assert torch.equal(results["decode"][2], results["prefill"][2])
     # auto picks a schedule and agrees
     y_auto = layer.forward(G.dev(xt))
     assert torch.equal(y_auto, y2)
@@ -155,7 +158,7 @@ def test_edge_inputs(bits):
     x[3] = 1e-42
     x[4, ::2] = np.inf
     x[4, 1::2] = -np.inf
-    for sch in ("generic", "prefill"):
+    for sch in ("generic", "prefill", "decode"):
         q, acc, y = G.check_forward(layer, pack, x, SCHEDULES[sch], what=f"edges/{sch}")
         assert not y[0].float().abs().max().item() > 0
     codes = G.host(q).astype(np.int32) + O.store_offset(bits)
@@ -183,3 +186,40 @@ def test_gps_scale_matches_oracle(K, N, L, n, bits, mode):
     assert np.allclose(got, s_ref, rtol=1e-5, atol=0), np.abs(got / s_ref - 1).max()
     if K == 64:
         assert got[5] == 1 and got[9] == 1
+
+
+# ---------------------------------------------------------------- decode step: grouped launch
+
+def test_decode_step_grouped():
+    """Three RAR-XXL-shaped layers (qkv, fc1, fc2 each) of configuration 4 at full width, M = 128 rows at one
+    position per layer, all nine linears in ONE launch; every code, accumulator and output is compared."""
+    specs = wl.config_linears(4, blocks=3)
+    packs, layers, problems, refs = [], [], [], []
+    for spec in specs:
+        w, b, xc, xt = G.make_case(spec)
+        t0 = wl.decode_position(spec)
+        pack = G.oracle_pack(spec, xc, w, b)
+        layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+        G.check_calibration(layer, pack)
+        q_ref, acc_ref, y_ref = O.forward(pack, xt, t0=t0)
+        q = layer.quantize(G.dev(xt), t0=t0)
+        assert np.array_equal(G.host(q), q_ref)
+        y = torch.zeros((spec.M, spec.N), dtype=torch.bfloat16, device=G.DEV)
+        acc = torch.zeros((spec.M, spec.N), dtype=torch.int32, device=G.DEV)
+        problems.append(dict(q=q, wq=layer.wq, dw=layer.dw, wsum=layer.wsum, delta=layer.delta[t0:t0 + 1],
+                             zp=layer.zp[t0:t0 + 1], a_bits=spec.a_bits, bias=layer.bias, y=y, L=1, acc_dbg=acc))
+        refs.append((acc_ref, y_ref, pack))
+        layers.append(layer)
+    group = P.LinearGroup(problems)
+    group.run()
+    torch.cuda.synchronize()
+    for spec, pr, (acc_ref, y_ref, pack) in zip(specs, problems, refs):
+        assert np.array_equal(G.host(pr["acc_dbg"]), acc_ref), f"{spec.name} layer {spec.layer}: accumulators differ"
+        G.check_bf16(pr["y"], y_ref, f"grouped {spec.name} {spec.layer}", pack["bias"])
+    # the single-launch decode schedule gives the same bits
+    pr = problems[4]
+    y1 = torch.empty_like(pr["y"])
+    P.stwq_linear(pr["q"], pr["wq"], pr["dw"], pr["wsum"], pr["delta"], pr["zp"], 8, pr["bias"], y1, 1, None, P.SCHEDULE_DECODE)
+    y2 = torch.empty_like(pr["y"])
+    P.stwq_linear(pr["q"], pr["wq"], pr["dw"], pr["wsum"], pr["delta"], pr["zp"], 8, pr["bias"], y2, 1)      # auto
+    assert torch.equal(y1, pr["y"]) and torch.equal(y2, pr["y"])
