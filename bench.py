@@ -78,7 +78,54 @@ def time_launches(fn, n_warm, n_iter):
     return ts[len(ts) // 2], sum(ts) / len(ts)
 
 
-def cpu_baseline(specs, sample_rows=1024):
+def decode_step(device, n_iter=30):
+    """Configuration 4: one RAR-XXL-shaped decode step, 24 layers x (qkv, fc1, fc2), M = 128 rows at one token
+    position per layer, 432.5 MB of distinct int8 weights streamed once per step by ONE grouped launch."""
+    import torch
+    import workloads as wl
+    import paper_2601_21238_amd as P
+    from paper_2601_21238_amd.layer import StwqLinear
+
+    specs = wl.config_linears(4)
+    t0 = time.time()
+    problems, keep = [], []
+    for spec in specs:
+        w, b = wl.make_weights(spec)
+        layer = StwqLinear(spec.N, spec.K, spec.L, spec.a_bits, spec.w_bits, device)
+        wd, bd = torch.from_numpy(w).to(device), torch.from_numpy(b).to(device)
+        xc = torch.from_numpy(wl.make_calibration(spec)).to(device)
+        s = layer.solve_scale(xc, wd) if spec.gps else None
+        layer.calibrate(xc, wd, s, bd)
+        pos = wl.decode_position(spec)
+        x = torch.from_numpy(wl.make_test_input(spec)).to(device)
+        q = layer.quantize(x, t0=pos)
+        y = torch.empty((spec.M, spec.N), dtype=torch.bfloat16, device=device)
+        problems.append(dict(q=q, wq=layer.wq, dw=layer.dw, wsum=layer.wsum, delta=layer.delta[pos:pos + 1],
+                             zp=layer.zp[pos:pos + 1], a_bits=spec.a_bits, bias=layer.bias, y=y, L=1))
+        keep.append((layer, x, pos))
+        del wd, xc
+    torch.cuda.synchronize()
+    log(f"decode step: 72 linears calibrated in {time.time() - t0:.1f} s")
+    group = P.LinearGroup(problems)
+    med, mean = time_launches(group.run, 5, n_iter)
+    w_bytes = float(sum(s.N * s.K for s in specs))
+    all_bytes = float(sum(s.N * s.K + s.M * s.K + 2 * s.M * s.N + 12 * s.N + 8 for s in specs))
+    ops = float(sum(2.0 * s.M * s.K * s.N for s in specs))
+
+    def quantize_all():
+        for (layer, x, pos), pr in zip(keep, problems):
+            layer.quantize(x, pr["q"], t0=pos)
+    qmed, _ = time_launches(quantize_all, 3, 10)
+    return {"workload": "config 4: RAR-XXL-shaped decode step, 72 linears, M = 128, one grouped launch",
+            "us": med * 1e6, "gbs": all_bytes / med / 1e9, "weight_gbs": w_bytes / med / 1e9,
+            "frac_hbm_peak": all_bytes / med / 1e9 / HBM_PEAK_GBS, "tops": ops / med / 1e12,
+            "roofline": {"bound": "hbm", "achieved": all_bytes / mean / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": all_bytes / mean / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "kernel": "stwq::linear_decode_kernel", "avg_launch_us": mean * 1e6},
+            "quantize_72_launches_us": qmed * 1e6}
+
+
+def cpu_baseline(specs, sample_rows=21760, repeats=3):
     """The oracle as it stands, timed on this host on a bounded sample: the first `sample_rows`
     rows of every linear of the block (quantize, exact integer product, dequantize)."""
     import workloads as wl
@@ -91,19 +138,20 @@ def cpu_baseline(specs, sample_rows=1024):
     ops, secs = 0.0, 0.0
     rng = np.random.default_rng(0)
     for spec in specs:
-        small = wl.shrink(spec, n_calib=2, batch=2)
+        small = wl.shrink(spec, n_calib=2)
         w, b = wl.make_weights(small)
         xc = wl.make_calibration(small)
         x = wl.make_test_input(small)[:sample_rows]
         s = rng.uniform(1.0, 20.0, spec.K).astype(np.float32) if spec.gps else None   # scale values do not change the cost
         pack = O.calibrate_layer(xc, w, b, spec.L, spec.a_bits, spec.w_bits, False, s=s)
-        t0 = time.perf_counter()
-        O.forward(pack, x)
-        secs += time.perf_counter() - t0
-        ops += 2.0 * x.shape[0] * spec.K * spec.N
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            O.forward(pack, x)
+            secs += time.perf_counter() - t0
+            ops += 2.0 * x.shape[0] * spec.K * spec.N
     return {"value": ops / secs / 1e12, "unit": "TOPS", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {sample_rows} rows of each of the 4 linears (quantize + exact integer product via fp64 "
-                      f"matmul + fp64 dequantize), {secs:.2f} s of CPU work"}
+            "sample": f"{repeats} passes over the first {sample_rows} rows of each of the 4 linears (quantize + exact integer "
+                      f"product via fp64 matmul + fp64 dequantize), {secs:.1f} s of CPU work"}
 
 
 def main() -> int:
@@ -204,7 +252,8 @@ def main() -> int:
     med, _ = time_launches(lambda: B.gps_fold_weights(wd, sd, 8, tmp.wq, tmp.dw, tmp.wsum, tmp.inv_s), 3, 20)
     extra["fold"] = {"us": med * 1e6, "gbs": 5.0 * wd.numel() / med / 1e9,
                      "frac_hbm_peak": 5.0 * wd.numel() / med / 1e9 / HBM_PEAK_GBS}
-    del xc
+    del xc, wd, tmp
+    extra["decode"] = decode_step(device)
 
     out = {
         "metric": "stwq_w8a8_linear_int8_tops",
