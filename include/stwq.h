@@ -165,7 +165,7 @@ typedef struct stwq_linear_problem {
  *   problems      HOST array of count descriptors (read during the call only: validation and grid size);
  *   problems_dev  DEVICE copy of the same count descriptors, made by the caller, 8-byte aligned; the
  *                 kernel reads it, so it must stay unchanged until the stream has passed this call.
- * Every problem must satisfy stwq_linear's rules and have K a multiple of 64; 1 <= count <= 4096. */
+ * Every problem must satisfy stwq_linear's rules and have K a multiple of 64; 1 <= count <= 1024. */
 STWQ_API int stwq_linear_grouped(const stwq_linear_problem* problems, int count,
                                  const stwq_linear_problem* problems_dev, void* stream);
 

@@ -157,10 +157,11 @@ struct TileCfg {
     static constexpr int kLoadsX = kTileM / 16 / kWaves;
     static constexpr int kLoads = kLoadsW + kLoadsX;
     static constexpr int kChunks = TI * 4;                // 16-byte bf16 chunks per staged output row
-    static constexpr int kWaveOut = TJ * 32 * TI * 64;    // bytes of one wave's staged output
-    static_assert((STAGES & (STAGES - 1)) == 0 && STAGES >= 2, "ring size must be a power of two");
+    static constexpr int kWaveStage = 8192;               // bytes of LDS one wave stages its output through, per pass
+    static constexpr int kJPerPass = kWaveStage / (32 * TI * 64);   // 32-token MFMA tiles staged per pass
     static_assert(kTileO % (16 * kWaves) == 0 && kTileM % (16 * kWaves) == 0, "tile rows must split over the waves");
-    static_assert(kWaves * kWaveOut <= kRing, "output staging must fit the ring");
+    static_assert(kJPerPass >= 1 && TJ % kJPerPass == 0, "staging passes must divide the token tiles");
+    static_assert(STAGES >= 4, "two slots stage the output while the others keep streaming");
     static_assert(kLoads * (STAGES - 1) <= 63, "vmcnt is a 6-bit counter");
 };
 typedef TileCfg<2, 4, 4, 2, 4> PrefillCfg;
@@ -210,16 +211,47 @@ __device__ __forceinline__ void issue_load(int l, const int8_t* const (&srcW)[C:
     }
 }
 
-// One K stage (two MFMA k-steps).
+// Per-lane addressing of one tile's operands.
+template <class C>
+struct TileSrc {
+    const int8_t* w[C::kLoadsW];
+    const int8_t* x[C::kLoadsX];
+};
+
+template <class C>
+__device__ __forceinline__ void tile_sources(const LinearArgs& p, long long m0, int o0, int wave, int lane, TileSrc<C>& t) {
+    // lane i of a direct-to-LDS load fills row i/4, physical chunk i%4 of its 16-row group
+#pragma unroll
+    for (int u = 0; u < C::kLoadsW; ++u) {
+        const int r = u * C::kWaves * 16 + wave * 16 + (lane >> 2);
+        const int lc = (lane & 3) ^ ((r >> 2) & 3);
+        t.w[u] = p.wq + static_cast<size_t>(min(o0 + r, p.N - 1)) * p.K + lc * 16;
+    }
+#pragma unroll
+    for (int u = 0; u < C::kLoadsX; ++u) {
+        const int r = u * C::kWaves * 16 + wave * 16 + (lane >> 2);
+        const int lc = (lane & 3) ^ ((r >> 2) & 3);
+        t.x[u] = p.q + static_cast<size_t>(min(m0 + r, static_cast<long long>(p.M) - 1)) * p.K + lc * 16;
+    }
+}
+
+// All direct-to-LDS loads of this wave for K stage `stage_idx` of a tile, into ring slot `slot`.
+template <class C>
+__device__ __forceinline__ void issue_stage(const TileSrc<C>& t, int stage_idx, int slot, int8_t* smem, int wave) {
+#pragma unroll
+    for (int l = 0; l < C::kLoads; ++l) issue_load<C>(l, t.w, t.x, stage_idx * kBK, smem + slot * C::kStage, wave);
+}
+
+// One K stage (two MFMA k-steps) of the tile whose stage 0 sits in ring slot `base`.
 template <class C, bool TAIL>
-__device__ __forceinline__ void stage_step(int s, int nk, int8_t* smem, unsigned lds_base,
-                                           const int8_t* const (&srcW)[C::kLoadsW], const int8_t* const (&srcX)[C::kLoadsX],
+__device__ __forceinline__ void stage_step(int s, int nk, int base, int8_t* smem, unsigned lds_base, const TileSrc<C>& t,
                                            const unsigned (&offA)[2], const unsigned (&offB)[2], int wave,
                                            v4i (&a0)[C::TI], v4i (&b0)[C::TJ], v4i (&a1)[C::TI], v4i (&b1)[C::TJ],
                                            v16i (&acc)[C::TI][C::TJ]) {
     constexpr int TI = C::TI, TJ = C::TJ;
-    const unsigned cur = lds_base + (s & (C::STAGES - 1)) * C::kStage;
-    const unsigned nxt = lds_base + ((s + 1) & (C::STAGES - 1)) * C::kStage;
+    const int slot = (base + s) % C::STAGES;
+    const unsigned cur = lds_base + slot * C::kStage;
+    const unsigned nxt = lds_base + ((slot + 1) % C::STAGES) * C::kStage;
     read_ops<TI, TJ>(cur + offA[1], cur + C::kOpW + offB[1], a1, b1);
     wait_ops<TI + TJ, TI, TJ>(a0, b0);
 #pragma unroll
@@ -234,16 +266,16 @@ __device__ __forceinline__ void stage_step(int s, int nk, int8_t* smem, unsigned
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     read_ops<TI, TJ>(nxt + offA[0], nxt + C::kOpW + offB[0], a0, b0);
-    // refill the stage every wave has just finished reading, one load per MFMA group
+    // refill the slot every wave has just finished reading, one load group per MFMA group
     const bool do_load = s + C::STAGES < nk;
-    int8_t* dst = smem + (s & (C::STAGES - 1)) * C::kStage;
+    int8_t* dst = smem + slot * C::kStage;
     const int k0 = (s + C::STAGES) * kBK;
     constexpr int per_slot = (C::kLoads + TI - 1) / TI;
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
         if (do_load) {
 #pragma unroll
-            for (int l = i * per_slot; l < (i + 1) * per_slot && l < C::kLoads; ++l) issue_load<C>(l, srcW, srcX, k0, dst, wave);
+            for (int l = i * per_slot; l < (i + 1) * per_slot && l < C::kLoads; ++l) issue_load<C>(l, t.w, t.x, k0, dst, wave);
         }
 #pragma unroll
         for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[j], acc[i][j], 0, 0, 0);
@@ -251,31 +283,104 @@ __device__ __forceinline__ void stage_step(int s, int nk, int8_t* smem, unsigned
     }
 }
 
-// Computes one output tile of problem p: rows m0.. of tokens, channels o0.. .
+// Dequantizes this wave's accumulators and writes them as bf16.  The values are transposed through
+// `stage` (8 KB of LDS private to the wave, 16-byte XOR swizzle) so that the global stores are
+// full row segments of 16 bytes per lane; kPasses passes of JP token tiles each.
 template <class C>
-__device__ __forceinline__ void compute_tile(const LinearArgs& p, long long m0, int o0, int8_t* smem,
-                                             float* c_dw, int* c_ws, float* c_bias) {
-    constexpr int TI = C::TI, TJ = C::TJ;
+__device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], int8_t* stage,
+                                         const float* c_dw, const int* c_ws, const float* c_bias, int lane, int wo, int wm) {
+    // On entry the only vector-memory operations in flight are the next tile's first loads.  They
+    // are waited for just before this tile's first store is issued (they have had the arithmetic of
+    // the first pass to land); after that only stores are outstanding, and nothing waits on them.
+    constexpr int TI = C::TI, TJ = C::TJ, JP = C::kJPerPass;
+    constexpr int kRowBytes = TI * 64;
+    const int l32 = lane & 31, hi = lane >> 5;
+    float dt[TJ];
+    int zs[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+        int m = static_cast<int>(m0) + wm * TJ * 32 + j * 32 + l32;
+        if (m >= p.M) m = p.M - 1;
+        const int t = m % p.L;
+        dt[j] = p.delta[t];
+        zs[j] = p.off - p.zp[t];            // minus the zero point of the stored codes
+    }
+    typedef __attribute__((address_space(1))) u4 global_u4;
+    constexpr int kRowsPerRead = 64 / C::kChunks;
+    constexpr int kReads = JP * 32 / kRowsPerRead;
+    const int cc = lane % C::kChunks;
+    const int o = o0 + wo * TI * 32 + cc * 8;
+    const bool o_ok = o < p.N;
+    const int cbase = wo * TI * 32 + 4 * hi;
+#pragma unroll
+    for (int pass = 0; pass < TJ / JP; ++pass) {
+        float4 dwv = *reinterpret_cast<const float4*>(c_dw + cbase);
+        int4 wsv = *reinterpret_cast<const int4*>(c_ws + cbase);
+        float4 bv = *reinterpret_cast<const float4*>(c_bias + cbase);
+#pragma unroll
+        for (int c = 0; c < C::kChunks; ++c) {       // c = 4 i + g: channels wo TI 32 + 8 c + 4 hi .. + 3
+            float4 dwn = dwv, bn = bv;
+            int4 wsn = wsv;
+            if (c + 1 < C::kChunks) {                // fetch the next group's constants under this group's arithmetic
+                dwn = *reinterpret_cast<const float4*>(c_dw + cbase + 8 * (c + 1));
+                wsn = *reinterpret_cast<const int4*>(c_ws + cbase + 8 * (c + 1));
+                bn = *reinterpret_cast<const float4*>(c_bias + cbase + 8 * (c + 1));
+            }
+            const int i = c >> 2, g = c & 3;
+#pragma unroll
+            for (int jj = 0; jj < JP; ++jj) {
+                const int j = pass * JP + jj;
+                const int row = jj * 32 + l32;
+                // exact integer part: acc - (z_t - off) wsum[o], one 24-bit multiply-add
+                const float y0 = fmaf(static_cast<float>((__mul24(zs[j], wsv.x) + acc[i][j][4 * g])), dt[j] * dwv.x, bv.x);
+                const float y1 = fmaf(static_cast<float>((__mul24(zs[j], wsv.y) + acc[i][j][4 * g + 1])), dt[j] * dwv.y, bv.y);
+                const float y2 = fmaf(static_cast<float>((__mul24(zs[j], wsv.z) + acc[i][j][4 * g + 2])), dt[j] * dwv.z, bv.z);
+                const float y3 = fmaf(static_cast<float>((__mul24(zs[j], wsv.w) + acc[i][j][4 * g + 3])), dt[j] * dwv.w, bv.w);
+                uint2 out;
+                out.x = pack_bf16(y0, y1);
+                out.y = pack_bf16(y2, y3);
+                *reinterpret_cast<uint2*>(stage + row * kRowBytes + ((c ^ (row & (C::kChunks - 1))) * 16) + hi * 8) = out;
+            }
+            dwv = dwn; wsv = wsn; bv = bn;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the same wave wrote and now reads: LDS operations of one wave complete in order
+        const long long mbase = m0 + wm * TJ * 32 + pass * JP * 32 + lane / C::kChunks;
+        global_u4* ybase = (global_u4*)(p.y + mbase * p.N + o);
+        const long long row_step = static_cast<long long>(kRowsPerRead) * p.N / 8;     // in 16-byte units
+        const int8_t* sbase = stage + (lane / C::kChunks) * kRowBytes;
+        if (pass == 0) wait_vm<0>();
+#pragma unroll
+        for (int r0 = 0; r0 < kReads; r0 += 4) {
+            u4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int row = (r0 + u) * kRowsPerRead + lane / C::kChunks;
+                v[u] = *reinterpret_cast<const u4*>(sbase + (r0 + u) * kRowsPerRead * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (o_ok && mbase + (r0 + u) * kRowsPerRead < p.M) ybase[(r0 + u) * row_step] = v[u];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// Persistent tile loop.  `sched.next(v, p, m0, o0)` advances the virtual tile id v (stride gridDim.x)
+// to this workgroup's next tile and returns false at the end.  The ring keeps streaming across
+// tiles: before a tile's epilogue, the first STAGES-2 stages of the NEXT tile are already requested
+// into the slots the finished tile no longer needs; the two remaining slots stage the bf16 output
+// and are refilled right after.  So neither the memory latency at the start of a tile nor most of
+// its epilogue leaves the load path idle.
+template <class C, class Sched>
+__device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, float* c_dw, int* c_ws, float* c_bias) {
+    constexpr int TI = C::TI, TJ = C::TJ, S = C::STAGES, E = 2;
+    static_assert(C::kWaves * C::kWaveStage == E * C::kStage, "output staging must be exactly two ring slots");
     const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>(smem));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int wo = wave % C::WO, wm = wave / C::WO;
 
-    // global sources of this lane's 16-byte pieces: lane i of a load fills row i/4, physical chunk i%4
-    const int8_t* srcW[C::kLoadsW];
-    const int8_t* srcX[C::kLoadsX];
-#pragma unroll
-    for (int u = 0; u < C::kLoadsW; ++u) {
-        const int r = u * C::kWaves * 16 + wave * 16 + (lane >> 2);
-        const int lc = (lane & 3) ^ ((r >> 2) & 3);
-        srcW[u] = p.wq + static_cast<size_t>(min(o0 + r, p.N - 1)) * p.K + lc * 16;
-    }
-#pragma unroll
-    for (int u = 0; u < C::kLoadsX; ++u) {
-        const int r = u * C::kWaves * 16 + wave * 16 + (lane >> 2);
-        const int lc = (lane & 3) ^ ((r >> 2) & 3);
-        srcX[u] = p.q + static_cast<size_t>(min(m0 + r, static_cast<long long>(p.M) - 1)) * p.K + lc * 16;
-    }
     // LDS byte offsets of this lane's MFMA operands for the two k-steps of a stage
     unsigned offA[2], offB[2];
     const int swz = (l32 >> 2) & 3;
@@ -286,157 +391,130 @@ __device__ __forceinline__ void compute_tile(const LinearArgs& p, long long m0, 
         offB[ks] = (wm * TJ * 32 + l32) * kBK + pc;
     }
 
-    v16i acc[TI][TJ];
+    long long v = blockIdx.x;
+    LinearArgs p;
+    long long m0;
+    int o0;
+    if (!sched.next(v, p, m0, o0)) return;
+    TileSrc<C> src;
+    tile_sources<C>(p, m0, o0, wave, lane, src);
+    int nk = p.K / kBK;
+    int base = 0;
+    bool first = true;
 #pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) acc[i][j] = (v16i){0};
+    for (int s = 0; s < S; ++s)
+        if (s < nk) issue_stage<C>(src, s, s, smem, wave);
 
-    // per-output-channel constants of this tile, read back in the epilogue
-    for (int r = tid; r < C::kTileO; r += C::kThreads) {
-        const int o = min(o0 + r, p.N - 1);
-        c_dw[r] = p.dw[o];
-        c_ws[r] = p.wsum[o];
-        c_bias[r] = p.bias ? p.bias[o] : 0.0f;
-    }
-
-    const int nk = p.K / kBK;
-#pragma unroll
-    for (int s = 0; s < C::STAGES; ++s)
-        if (s < nk) {
-#pragma unroll
-            for (int l = 0; l < C::kLoads; ++l) issue_load<C>(l, srcW, srcX, s * kBK, smem + s * C::kStage, wave);
+    while (true) {
+        // per-output-channel constants of this tile (read in the epilogue, after many barriers)
+        for (int r = tid; r < C::kTileO; r += C::kThreads) {
+            const int o = min(o0 + r, p.N - 1);
+            c_dw[r] = p.dw[o];
+            c_ws[r] = p.wsum[o];
+            c_bias[r] = p.bias ? p.bias[o] : 0.0f;
         }
-    if (nk >= C::STAGES) wait_vm<C::kLoads * (C::STAGES - 1)>();
-    else wait_vm<0>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    v4i a0[TI], b0[TJ], a1[TI], b1[TJ];
-    read_ops<TI, TJ>(lds_base + offA[0], lds_base + C::kOpW + offB[0], a0, b0);
+        v16i acc[TI][TJ];
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) acc[i][j] = (v16i){0};
 
-    int s = 0;
-    const int n_steady = nk - (C::STAGES - 1);
-    for (; s < n_steady; ++s) stage_step<C, false>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
-    for (; s < nk; ++s) stage_step<C, true>(s, nk, smem, lds_base, srcW, srcX, offA, offB, wave, a0, b0, a1, b1, acc);
-    wait_ops<0, TI, TJ>(a0, b0);   // the last prefetch read a stage nobody filled; drain it
-
-    if (p.acc_dbg) {   // raw accumulators for the bit-exact check (debug path, not tuned)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-            const long long m = m0 + wm * TJ * 32 + j * 32 + l32;
-#pragma unroll
-            for (int i = 0; i < TI; ++i)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int o4 = o0 + wo * TI * 32 + i * 32 + 8 * g + 4 * hi;
-                    if (m < p.M && o4 < p.N)
-                        *reinterpret_cast<int4*>(p.acc_dbg + m * p.N + o4) =
-                            make_int4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-                }
+        if (first) {   // stage 0 must have landed; later tiles had theirs waited for in the previous epilogue
+            if (nk >= S) wait_vm<C::kLoads * (S - 1)>();
+            else wait_vm<0>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            first = false;
         }
-    }
-
-    // ---- epilogue: dequantize, stage bf16 through this wave's slice of the ring, store full rows ----
-    __syncthreads();   // every wave is done reading operands; the constants table is complete
-    int8_t* stage = smem + wave * C::kWaveOut;
-    constexpr int kRowBytes = TI * 64;
-    float dt[TJ];
-    int zs[TJ];
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) {
-        int m = static_cast<int>(m0) + wm * TJ * 32 + j * 32 + l32;
-        if (m >= p.M) m = p.M - 1;
-        const int t = m % p.L;
-        dt[j] = p.delta[t];
-        zs[j] = p.zp[t] - p.off;
-    }
-    const int cbase = wo * TI * 32 + 4 * hi;
-    float4 dwv = *reinterpret_cast<const float4*>(c_dw + cbase);
-    int4 wsv = *reinterpret_cast<const int4*>(c_ws + cbase);
-    float4 bv = *reinterpret_cast<const float4*>(c_bias + cbase);
-#pragma unroll
-    for (int c = 0; c < C::kChunks; ++c) {       // c = 4 i + g: channels wo TI 32 + 8 c + 4 hi .. + 3
-        float4 dwn = dwv, bn = bv;
-        int4 wsn = wsv;
-        if (c + 1 < C::kChunks) {                // fetch the next group's constants under this group's arithmetic
-            dwn = *reinterpret_cast<const float4*>(c_dw + cbase + 8 * (c + 1));
-            wsn = *reinterpret_cast<const int4*>(c_ws + cbase + 8 * (c + 1));
-            bn = *reinterpret_cast<const float4*>(c_bias + cbase + 8 * (c + 1));
-        }
-        const int i = c >> 2, g = c & 3;
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-            const int row = j * 32 + l32;
-            const float y0 = fmaf(static_cast<float>(acc[i][j][4 * g] - __mul24(zs[j], wsv.x)), dt[j] * dwv.x, bv.x);
-            const float y1 = fmaf(static_cast<float>(acc[i][j][4 * g + 1] - __mul24(zs[j], wsv.y)), dt[j] * dwv.y, bv.y);
-            const float y2 = fmaf(static_cast<float>(acc[i][j][4 * g + 2] - __mul24(zs[j], wsv.z)), dt[j] * dwv.z, bv.z);
-            const float y3 = fmaf(static_cast<float>(acc[i][j][4 * g + 3] - __mul24(zs[j], wsv.w)), dt[j] * dwv.w, bv.w);
-            uint2 out;
-            out.x = pack_bf16(y0, y1);
-            out.y = pack_bf16(y2, y3);
-            *reinterpret_cast<uint2*>(stage + row * kRowBytes + ((c ^ (row & (C::kChunks - 1))) * 16) + hi * 8) = out;
-        }
-        dwv = dwn; wsv = wsn; bv = bn;
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    // the same wave wrote and now reads: LDS operations of one wave complete in order
-    constexpr int kRowsPerPass = 64 / C::kChunks;
-    constexpr int kPasses = TJ * 32 / kRowsPerPass;
-    const int cc = lane % C::kChunks;
-    const int o = o0 + wo * TI * 32 + cc * 8;
-    typedef __attribute__((address_space(1))) u4 global_u4;
-    global_u4* ybase = (global_u4*)(p.y + (m0 + wm * TJ * 32 + lane / C::kChunks) * p.N + o);
-    const long long row_step = static_cast<long long>(kRowsPerPass) * p.N / 8;     // in 16-byte units
-    const int8_t* sbase = stage + (lane / C::kChunks) * kRowBytes;
-    const bool o_ok = o < p.N;
-#pragma unroll
-    for (int r0 = 0; r0 < kPasses; r0 += 4) {
-        u4 v0, v1, v2, v3;
+        v4i a0[TI], b0[TJ], a1[TI], b1[TJ];
         {
-            const int row = (r0 + 0) * kRowsPerPass + lane / C::kChunks;
-            v0 = *reinterpret_cast<const u4*>(sbase + (r0 + 0) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
+            const unsigned first = lds_base + (base % S) * C::kStage;
+            read_ops<TI, TJ>(first + offA[0], first + C::kOpW + offB[0], a0, b0);
         }
+        int s = 0;
+        const int n_steady = nk - (S - 1);
+        for (; s < n_steady; ++s) stage_step<C, false>(s, nk, base, smem, lds_base, src, offA, offB, wave, a0, b0, a1, b1, acc);
+        for (; s < nk; ++s) stage_step<C, true>(s, nk, base, smem, lds_base, src, offA, offB, wave, a0, b0, a1, b1, acc);
+        wait_ops<0, TI, TJ>(a0, b0);   // the last prefetch read a slot nobody filled; drain it
+
+        if (p.acc_dbg) {   // raw accumulators for the bit-exact check (debug path, not tuned)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) {
+                const long long m = m0 + wm * TJ * 32 + j * 32 + l32;
+#pragma unroll
+                for (int i = 0; i < TI; ++i)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int o4 = o0 + wo * TI * 32 + i * 32 + 8 * g + 4 * hi;
+                        if (m < p.M && o4 < p.N)
+                            *reinterpret_cast<int4*>(p.acc_dbg + m * p.N + o4) =
+                                make_int4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                    }
+            }
+        }
+
+        // next tile of this workgroup
+        v += gridDim.x;
+        LinearArgs pn;
+        long long m0n;
+        int o0n;
+        const bool more = sched.next(v, pn, m0n, o0n);
+        TileSrc<C> srcn;
+        int nkn = 0;
+        const int b2 = (base + nk) % S;              // ring slot where the next tile's stage 0 goes
+        __syncthreads();                             // every wave is done reading operands; constants table complete
+        if (more) {
+            tile_sources<C>(pn, m0n, o0n, wave, lane, srcn);
+            nkn = pn.K / kBK;
+#pragma unroll
+            for (int q = 0; q < S - E; ++q)
+                if (q < nkn) issue_stage<C>(srcn, q, (b2 + q) % S, smem, wave);
+        }
+        // output staging: the two slots that follow in ring order; a wave's 8 KB lies inside one slot
         {
-            const int row = (r0 + 1) * kRowsPerPass + lane / C::kChunks;
-            v1 = *reinterpret_cast<const u4*>(sbase + (r0 + 1) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
+            constexpr int waves_per_slot = C::kStage / C::kWaveStage;
+            const int slot = (b2 + (S - E) + wave / waves_per_slot) % S;
+            int8_t* stage = smem + slot * C::kStage + (wave % waves_per_slot) * C::kWaveStage;
+            epilogue<C>(p, m0, o0, acc, stage, c_dw, c_ws, c_bias, lane, wo, wm);
         }
-        {
-            const int row = (r0 + 2) * kRowsPerPass + lane / C::kChunks;
-            v2 = *reinterpret_cast<const u4*>(sbase + (r0 + 2) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
-        }
-        {
-            const int row = (r0 + 3) * kRowsPerPass + lane / C::kChunks;
-            v3 = *reinterpret_cast<const u4*>(sbase + (r0 + 3) * kRowsPerPass * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
-        }
-        const long long mrow = m0 + wm * TJ * 32 + r0 * kRowsPerPass + lane / C::kChunks;
-        if (o_ok && mrow < p.M) ybase[(r0 + 0) * row_step] = v0;
-        if (o_ok && mrow + kRowsPerPass < p.M) ybase[(r0 + 1) * row_step] = v1;
-        if (o_ok && mrow + 2 * kRowsPerPass < p.M) ybase[(r0 + 2) * row_step] = v2;
-        if (o_ok && mrow + 3 * kRowsPerPass < p.M) ybase[(r0 + 3) * row_step] = v3;
-        __builtin_amdgcn_sched_barrier(0);
+        if (!more) break;
+        __syncthreads();                             // staging slots and constants table are free again; every wave's
+                                                     // early loads of the next tile have landed (waited in the epilogue)
+#pragma unroll
+        for (int q = S - E; q < S; ++q)
+            if (q < nkn) issue_stage<C>(srcn, q, (b2 + q) % S, smem, wave);
+        p = pn; m0 = m0n; o0 = o0n; src = srcn; nk = nkn; base = b2;
     }
 }
 
-// Prefill launch: one tile per workgroup.  Workgroups are dealt round-robin to the 8 XCDs (each with
-// its own L2); the 32 workgroups one XCD runs together are mapped to a compact patch_m x patch_o
-// patch of tiles so that they share operand rows in that L2.
-__global__ __launch_bounds__(PrefillCfg::kThreads) void linear_prefill_kernel(LinearArgs p, int tiles_m, int tiles_o, int patch_o,
-                                                                              int patch_m) {
-    typedef PrefillCfg C;
-    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
-    __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
-    __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
-    __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
-    const int bid = blockIdx.x;
-    const int xcd = bid & 7, j = bid >> 3;
-    const int patch = (j >> 5) * 8 + xcd, idx = j & 31;
-    const int npo = (tiles_o + patch_o - 1) / patch_o;
-    const int po = patch % npo, pm = patch / npo;
-    const int tile_o = po * patch_o + idx % patch_o;
-    const int tile_m = pm * patch_m + idx / patch_o;
-    if (tile_o >= tiles_o || tile_m >= tiles_m) return;
-    compute_tile<C>(p, static_cast<long long>(tile_m) * C::kTileM, tile_o * C::kTileO, smem, c_dw, c_ws, c_bias);
-}
+// Prefill schedule: virtual workgroup ids are dealt round-robin to the 8 XCDs (each with its own
+// L2) exactly like hardware workgroup ids; the 32 ids an XCD runs together are mapped to a compact
+// patch_m x patch_o patch of tiles so that they share operand rows in that L2.
+struct PrefillSched {
+    LinearArgs p;
+    int tiles_m, tiles_o, patch_o, patch_m;
+    long long n_virtual;
+    __device__ __forceinline__ bool next(long long& v, LinearArgs& out, long long& m0, int& o0) const {
+        for (; v < n_virtual; v += gridDim.x) {
+            const int xcd = static_cast<int>(v & 7);
+            const long long j = v >> 3;
+            const long long patch = (j >> 5) * 8 + xcd;
+            const int idx = static_cast<int>(j & 31);
+            const int npo = (tiles_o + patch_o - 1) / patch_o;
+            const int po = static_cast<int>(patch % npo);
+            const long long pm = patch / npo;
+            const int tile_o = po * patch_o + idx % patch_o;
+            const long long tile_m = pm * patch_m + idx / patch_o;
+            if (tile_o < tiles_o && tile_m < tiles_m) {
+                out = p;
+                m0 = tile_m * PrefillCfg::kTileM;
+                o0 = tile_o * PrefillCfg::kTileO;
+                return true;
+            }
+        }
+        return false;
+    }
+};
 
 __device__ __forceinline__ LinearArgs args_of(const stwq_linear_problem& q) {
     LinearArgs p;
@@ -446,31 +524,66 @@ __device__ __forceinline__ LinearArgs args_of(const stwq_linear_problem& q) {
     return p;
 }
 
-// Decode launch, single problem or a group of problems in one launch: workgroup b takes tile b of
-// the concatenated tile lists (channel tiles fastest within a problem).
-__global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(LinearArgs single, const stwq_linear_problem* problems,
-                                                                            int count) {
+// Decode schedule, one problem or a group: tile v of the concatenated tile lists (channel tiles
+// fastest within a problem).  `prefix` (LDS, count + 1 entries) holds the running tile counts.
+constexpr int kMaxGroup = 1024;
+struct DecodeSched {
+    LinearArgs single;
+    const stwq_linear_problem* problems;
+    int count;
+    long long n_tiles;
+    const int* prefix;      // set by the kernel
+    int cursor;             // problem the previous tile belonged to (tiles are visited in increasing order)
+    __device__ __forceinline__ bool next(long long& v, LinearArgs& out, long long& m0, int& o0) {
+        typedef DecodeCfg C;
+        if (v >= n_tiles) return false;
+        long long tile = v;
+        if (problems) {
+            int i = cursor;
+            while (tile >= prefix[i + 1]) ++i;
+            cursor = i;
+            tile -= prefix[i];
+            out = args_of(problems[i]);
+        } else {
+            out = single;
+        }
+        const int tiles_o = (out.N + C::kTileO - 1) / C::kTileO;
+        const long long tile_m = tile / tiles_o;
+        m0 = tile_m * C::kTileM;
+        o0 = static_cast<int>(tile - tile_m * tiles_o) * C::kTileO;
+        return true;
+    }
+};
+
+__global__ __launch_bounds__(PrefillCfg::kThreads) void linear_prefill_kernel(PrefillSched sched) {
+    typedef PrefillCfg C;
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+    __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
+    __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
+    __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
+    persistent_tiles<C>(sched, smem, c_dw, c_ws, c_bias);
+}
+
+__global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(DecodeSched sched) {
     typedef DecodeCfg C;
     extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
     __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
     __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
     __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
-    LinearArgs p = single;
-    int tile = blockIdx.x;
-    if (problems) {
-        int i = 0;
-        for (; i < count; ++i) {
-            const int tiles = ((problems[i].M + C::kTileM - 1) / C::kTileM) * ((problems[i].N + C::kTileO - 1) / C::kTileO);
-            if (tile < tiles) break;
-            tile -= tiles;
+    __shared__ int prefix[kMaxGroup + 1];
+    if (sched.problems) {
+        for (int i = threadIdx.x; i < sched.count; i += C::kThreads)
+            prefix[i + 1] = ((sched.problems[i].M + C::kTileM - 1) / C::kTileM) * ((sched.problems[i].N + C::kTileO - 1) / C::kTileO);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            prefix[0] = 0;
+            for (int i = 0; i < sched.count; ++i) prefix[i + 1] += prefix[i];
         }
-        if (i == count) return;
-        p = args_of(problems[i]);
+        __syncthreads();
     }
-    const int tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
-    const int tile_m = tile / tiles_o, tile_o = tile - tile_m * tiles_o;
-    if (static_cast<long long>(tile_m) * C::kTileM >= p.M) return;
-    compute_tile<C>(p, static_cast<long long>(tile_m) * C::kTileM, tile_o * C::kTileO, smem, c_dw, c_ws, c_bias);
+    sched.prefix = prefix;
+    sched.cursor = 0;
+    persistent_tiles<C>(sched, smem, c_dw, c_ws, c_bias);
 }
 
 static int check_linear_args(const char* who, const int8_t* q, int64_t M, int K, int N, int L, const int8_t* wq,
@@ -499,6 +612,30 @@ static int set_ring(Kernel kernel, int bytes) {
     return STWQ_OK;
 }
 
+// Number of compute units of the current device: the persistent kernels launch one workgroup per CU
+// (their LDS ring allows no more), each looping over tiles.
+static int compute_units(int* out) {
+    int dev = 0, n = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess || n <= 0) return stwq::fail(STWQ_EHIP, "cannot query the compute-unit count: %s", hipGetErrorString(e));
+    *out = n;
+    return STWQ_OK;
+}
+
+static int launch_decode(const stwq::DecodeSched& sched, hipStream_t s) {
+    using namespace stwq;
+    typedef DecodeCfg C;
+    static const int attr = set_ring(linear_decode_kernel, C::kRing);
+    if (attr != STWQ_OK) return attr;
+    int cus = 0;
+    const int rc = compute_units(&cus);
+    if (rc != STWQ_OK) return rc;
+    const long long grid = sched.n_tiles < cus ? sched.n_tiles : cus;
+    linear_decode_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(sched);
+    return launch_status("linear_decode_kernel");
+}
+
 static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s) {
     using namespace stwq;
     const long long M = p.M;
@@ -511,27 +648,35 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
         typedef PrefillCfg C;
         static const int attr = set_ring(linear_prefill_kernel, C::kRing);
         if (attr != STWQ_OK) return attr;
-        const int tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
-        const long long tiles_m = (M + C::kTileM - 1) / C::kTileM;
+        PrefillSched sched;
+        sched.p = p;
+        sched.tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
+        sched.tiles_m = static_cast<int>((M + C::kTileM - 1) / C::kTileM);
         // patch of tiles one XCD works on at a time: patch_o x patch_m = 32
-        int patch_o = tiles_o < 4 ? tiles_o : 4;
+        int patch_o = sched.tiles_o < 4 ? sched.tiles_o : 4;
         while (32 % patch_o) --patch_o;
-        const int patch_m = 32 / patch_o;
-        const long long n_patches = ((tiles_o + patch_o - 1) / patch_o) * ((tiles_m + patch_m - 1) / patch_m);
-        const long long n_blocks = ((n_patches + 7) / 8) * 8 * 32;
-        STWQ_REQUIRE(n_blocks <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
-        linear_prefill_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(C::kThreads), C::kRing, s>>>(
-            p, static_cast<int>(tiles_m), tiles_o, patch_o, patch_m);
+        sched.patch_o = patch_o;
+        sched.patch_m = 32 / patch_o;
+        const long long n_patches = static_cast<long long>((sched.tiles_o + patch_o - 1) / patch_o) *
+                                    ((sched.tiles_m + sched.patch_m - 1) / sched.patch_m);
+        sched.n_virtual = ((n_patches + 7) / 8) * 8 * 32;
+        int cus = 0;
+        const int rc = compute_units(&cus);
+        if (rc != STWQ_OK) return rc;
+        const long long grid = sched.n_virtual < cus ? sched.n_virtual : cus;
+        linear_prefill_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(sched);
         return launch_status("linear_prefill_kernel");
     }
     if (schedule == STWQ_SCHEDULE_DECODE) {
         typedef DecodeCfg C;
-        static const int attr = set_ring(linear_decode_kernel, C::kRing);
-        if (attr != STWQ_OK) return attr;
-        const long long n_blocks = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
-        STWQ_REQUIRE(n_blocks <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
-        linear_decode_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(C::kThreads), C::kRing, s>>>(p, nullptr, 0);
-        return launch_status("linear_decode_kernel");
+        DecodeSched sched;
+        sched.single = p;
+        sched.problems = nullptr;
+        sched.count = 0;
+        sched.n_tiles = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
+        sched.prefix = nullptr;
+        sched.cursor = 0;
+        return launch_decode(sched, s);
     }
     if (schedule == STWQ_SCHEDULE_GENERIC) {
         const long long gx = (M + 63) / 64;
@@ -549,8 +694,14 @@ extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int coun
     typedef DecodeCfg C;
     clear_error();
     STWQ_REQUIRE(problems && problems_dev, "stwq_linear_grouped: null pointer");
-    STWQ_REQUIRE(count > 0 && count <= 4096, "stwq_linear_grouped: count = %d must be in 1 .. 4096", count);
-    long long n_blocks = 0;
+    STWQ_REQUIRE(count > 0 && count <= kMaxGroup, "stwq_linear_grouped: count = %d must be in 1 .. %d", count, kMaxGroup);
+    DecodeSched sched;
+    sched.single = LinearArgs{};
+    sched.problems = problems_dev;
+    sched.count = count;
+    sched.n_tiles = 0;
+    sched.prefix = nullptr;
+    sched.cursor = 0;
     for (int i = 0; i < count; ++i) {
         const stwq_linear_problem& q = problems[i];
         const int rc = check_linear_args("stwq_linear_grouped", q.q_dev, q.M, q.K, q.N, q.L, q.wq_dev, q.dw_dev, q.wsum_dev,
@@ -558,14 +709,10 @@ extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int coun
         if (rc != STWQ_OK) return rc;
         if (q.K % kBK != 0)
             return fail(STWQ_EUNSUPPORTED, "stwq_linear_grouped: problem %d has K = %d, needs K %% %d == 0", i, q.K, kBK);
-        n_blocks += static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+        sched.n_tiles += static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
     }
-    STWQ_REQUIRE(n_blocks <= 0x7FFFFFFFLL, "stwq_linear_grouped: too many tiles");
-    static const int attr = set_ring(linear_decode_kernel, C::kRing);
-    if (attr != STWQ_OK) return attr;
-    linear_decode_kernel<<<dim3(static_cast<unsigned>(n_blocks)), dim3(C::kThreads), C::kRing, static_cast<hipStream_t>(stream)>>>(
-        LinearArgs{}, problems_dev, count);
-    return launch_status("linear_decode_kernel (grouped)");
+    STWQ_REQUIRE(sched.n_tiles <= 0x7FFFFFFFLL, "stwq_linear_grouped: too many tiles");
+    return launch_decode(sched, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,
