@@ -10,6 +10,7 @@
 // runs of four consecutive output channels, which are contiguous in the row-major [M, N] output.
 // Inside one MFMA both operands take the same 16-byte K chunk per lane, and integer sums commute,
 // so any consistent assignment of K chunks to lanes gives the exact result.
+#include <algorithm>
 #include <utility>
 
 #include "common.h"
@@ -366,6 +367,33 @@ __device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int 
     }
 }
 
+// Per-output-channel constants of a tile: fetched into registers early (ahead of the tile's operand
+// loads, so that nothing has to wait behind those), written to the LDS table when the table is free.
+struct TileConsts {
+    float dw, bias;
+    int ws;
+};
+template <class C>
+__device__ __forceinline__ TileConsts load_consts(const LinearArgs& p, int o0, int tid) {
+    static_assert(C::kTileO <= C::kThreads, "one table row per thread");
+    TileConsts c = {0.0f, 0.0f, 0};
+    if (tid < C::kTileO) {
+        const int o = min(o0 + tid, p.N - 1);
+        c.dw = p.dw[o];
+        c.ws = p.wsum[o];
+        c.bias = p.bias ? p.bias[o] : 0.0f;
+    }
+    return c;
+}
+template <class C>
+__device__ __forceinline__ void store_consts(const TileConsts& c, int tid, float* c_dw, int* c_ws, float* c_bias) {
+    if (tid < C::kTileO) {
+        c_dw[tid] = c.dw;
+        c_ws[tid] = c.ws;
+        c_bias[tid] = c.bias;
+    }
+}
+
 // Persistent tile loop.  `sched.next(v, p, m0, o0)` advances the virtual tile id v (stride gridDim.x)
 // to this workgroup's next tile and returns false at the end.  The ring keeps streaming across
 // tiles: before a tile's epilogue, the first STAGES-2 stages of the NEXT tile are already requested
@@ -375,7 +403,8 @@ __device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int 
 template <class C, class Sched>
 __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, float* c_dw, int* c_ws, float* c_bias) {
     constexpr int TI = C::TI, TJ = C::TJ, S = C::STAGES, E = 2;
-    static_assert(C::kWaves * C::kWaveStage == E * C::kStage, "output staging must be exactly two ring slots");
+    static_assert(C::kWaves * C::kWaveStage <= E * C::kStage && C::kStage % C::kWaveStage == 0,
+                  "output staging must fit two ring slots");
     const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>(smem));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
@@ -401,18 +430,16 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
     int nk = p.K / kBK;
     int base = 0;
     bool first = true;
+    TileConsts consts = load_consts<C>(p, o0, tid);
 #pragma unroll
     for (int s = 0; s < S; ++s)
         if (s < nk) issue_stage<C>(src, s, s, smem, wave);
+    store_consts<C>(consts, tid, c_dw, c_ws, c_bias);
 
     while (true) {
-        // per-output-channel constants of this tile (read in the epilogue, after many barriers)
-        for (int r = tid; r < C::kTileO; r += C::kThreads) {
-            const int o = min(o0 + r, p.N - 1);
-            c_dw[r] = p.dw[o];
-            c_ws[r] = p.wsum[o];
-            c_bias[r] = p.bias ? p.bias[o] : 0.0f;
-        }
+        // loop control is the same in every lane; keep it in scalar registers
+        nk = __builtin_amdgcn_readfirstlane(nk);
+        base = __builtin_amdgcn_readfirstlane(base);
         v16i acc[TI][TJ];
 #pragma unroll
         for (int i = 0; i < TI; ++i)
@@ -464,6 +491,7 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
         const int b2 = (base + nk) % S;              // ring slot where the next tile's stage 0 goes
         __syncthreads();                             // every wave is done reading operands; constants table complete
         if (more) {
+            consts = load_consts<C>(pn, o0n, tid);
             tile_sources<C>(pn, m0n, o0n, wave, lane, srcn);
             nkn = pn.K / kBK;
 #pragma unroll
@@ -480,6 +508,7 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
         if (!more) break;
         __syncthreads();                             // staging slots and constants table are free again; every wave's
                                                      // early loads of the next tile have landed (waited in the epilogue)
+        store_consts<C>(consts, tid, c_dw, c_ws, c_bias);
 #pragma unroll
         for (int q = S - E; q < S; ++q)
             if (q < nkn) issue_stage<C>(srcn, q, (b2 + q) % S, smem, wave);
@@ -490,7 +519,8 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
 // Prefill schedule: virtual workgroup ids are dealt round-robin to the 8 XCDs (each with its own
 // L2) exactly like hardware workgroup ids; the 32 ids an XCD runs together are mapped to a compact
 // patch_m x patch_o patch of tiles so that they share operand rows in that L2.
-struct PrefillSched {
+template <class C>
+struct PatchSched {
     LinearArgs p;
     int tiles_m, tiles_o, patch_o, patch_m;
     long long n_virtual;
@@ -507,8 +537,8 @@ struct PrefillSched {
             const long long tile_m = pm * patch_m + idx / patch_o;
             if (tile_o < tiles_o && tile_m < tiles_m) {
                 out = p;
-                m0 = tile_m * PrefillCfg::kTileM;
-                o0 = tile_o * PrefillCfg::kTileO;
+                m0 = tile_m * C::kTileM;
+                o0 = tile_o * C::kTileO;
                 return true;
             }
         }
@@ -516,41 +546,63 @@ struct PrefillSched {
     }
 };
 
+typedef PatchSched<PrefillCfg> PrefillSched;
+
+// The descriptor is the same for every lane, but it is read with vector loads (the compiler cannot
+// prove that the kernel's own stores leave it alone).  Passing each field through readfirstlane
+// moves it to scalar registers, so that sizes and pointers of a tile are scalar again and the K
+// loop keeps scalar control flow.
+template <class T>
+__device__ __forceinline__ T* uniform_ptr(T* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    return reinterpret_cast<T*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
 __device__ __forceinline__ LinearArgs args_of(const stwq_linear_problem& q) {
     LinearArgs p;
-    p.q = q.q_dev; p.wq = q.wq_dev; p.dw = q.dw_dev; p.wsum = q.wsum_dev; p.delta = q.delta_dev; p.zp = q.zp_dev;
-    p.bias = q.bias_dev; p.y = q.y_bf16_dev; p.acc_dbg = q.acc_dbg_dev;
-    p.M = q.M; p.K = q.K; p.N = q.N; p.L = q.L; p.off = q.a_bits == 8 ? 128 : 0;
+    p.q = uniform_ptr(q.q_dev); p.wq = uniform_ptr(q.wq_dev); p.dw = uniform_ptr(q.dw_dev); p.wsum = uniform_ptr(q.wsum_dev);
+    p.delta = uniform_ptr(q.delta_dev); p.zp = uniform_ptr(q.zp_dev); p.bias = uniform_ptr(q.bias_dev);
+    p.y = uniform_ptr(q.y_bf16_dev); p.acc_dbg = uniform_ptr(q.acc_dbg_dev);
+    p.M = __builtin_amdgcn_readfirstlane(q.M); p.K = __builtin_amdgcn_readfirstlane(q.K);
+    p.N = __builtin_amdgcn_readfirstlane(q.N); p.L = __builtin_amdgcn_readfirstlane(q.L);
+    p.off = __builtin_amdgcn_readfirstlane(q.a_bits) == 8 ? 128 : 0;
     return p;
 }
 
 // Decode schedule, one problem or a group: tile v of the concatenated tile lists (channel tiles
 // fastest within a problem).  `prefix` (LDS, count + 1 entries) holds the running tile counts.
 constexpr int kMaxGroup = 1024;
+// Problems sorted by decreasing K: the long tiles are dealt out first, so the static round-robin over
+// workgroups ends balanced (longest-processing-time-first).
+struct GroupOrder {
+    uint16_t v[kMaxGroup];
+};
 struct DecodeSched {
     LinearArgs single;
     const stwq_linear_problem* problems;
+    const GroupOrder* order;   // kernel argument space
+    const int* prefix;         // LDS, count + 1 running tile counts in `order`
     int count;
     long long n_tiles;
-    const int* prefix;      // set by the kernel
-    int cursor;             // problem the previous tile belonged to (tiles are visited in increasing order)
+    int cursor;                // position in `order` of the previous tile (tiles are visited in increasing order)
     __device__ __forceinline__ bool next(long long& v, LinearArgs& out, long long& m0, int& o0) {
         typedef DecodeCfg C;
         if (v >= n_tiles) return false;
-        long long tile = v;
+        int tile = static_cast<int>(v);
         if (problems) {
             int i = cursor;
-            while (tile >= prefix[i + 1]) ++i;
+            while (tile >= __builtin_amdgcn_readfirstlane(prefix[i + 1])) ++i;   // scalar condition: a uniform loop
             cursor = i;
-            tile -= prefix[i];
-            out = args_of(problems[i]);
+            tile -= __builtin_amdgcn_readfirstlane(prefix[i]);
+            out = args_of(problems[order->v[i]]);
         } else {
             out = single;
         }
         const int tiles_o = (out.N + C::kTileO - 1) / C::kTileO;
-        const long long tile_m = tile / tiles_o;
-        m0 = tile_m * C::kTileM;
-        o0 = static_cast<int>(tile - tile_m * tiles_o) * C::kTileO;
+        const int tile_m = tile / tiles_o;
+        m0 = static_cast<long long>(tile_m) * C::kTileM;
+        o0 = (tile - tile_m * tiles_o) * C::kTileO;
         return true;
     }
 };
@@ -564,24 +616,33 @@ __global__ __launch_bounds__(PrefillCfg::kThreads) void linear_prefill_kernel(Pr
     persistent_tiles<C>(sched, smem, c_dw, c_ws, c_bias);
 }
 
-__global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(DecodeSched sched) {
+__global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(const LinearArgs single, const stwq_linear_problem* problems,
+                                                                            int count, long long n_tiles, const GroupOrder order) {
     typedef DecodeCfg C;
     extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
     __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
     __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
     __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
     __shared__ int prefix[kMaxGroup + 1];
-    if (sched.problems) {
-        for (int i = threadIdx.x; i < sched.count; i += C::kThreads)
-            prefix[i + 1] = ((sched.problems[i].M + C::kTileM - 1) / C::kTileM) * ((sched.problems[i].N + C::kTileO - 1) / C::kTileO);
+    if (problems) {
+        for (int i = threadIdx.x; i < count; i += C::kThreads) {
+            const stwq_linear_problem& q = problems[order.v[i]];
+            prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+        }
         __syncthreads();
         if (threadIdx.x == 0) {
             prefix[0] = 0;
-            for (int i = 0; i < sched.count; ++i) prefix[i + 1] += prefix[i];
+            for (int i = 0; i < count; ++i) prefix[i + 1] += prefix[i];
         }
         __syncthreads();
     }
+    DecodeSched sched;
+    sched.single = single;
+    sched.problems = problems;
+    sched.order = &order;
     sched.prefix = prefix;
+    sched.count = count;
+    sched.n_tiles = n_tiles;
     sched.cursor = 0;
     persistent_tiles<C>(sched, smem, c_dw, c_ws, c_bias);
 }
@@ -615,15 +676,24 @@ static int set_ring(Kernel kernel, int bytes) {
 // Number of compute units of the current device: the persistent kernels launch one workgroup per CU
 // (their LDS ring allows no more), each looping over tiles.
 static int compute_units(int* out) {
-    int dev = 0, n = 0;
+    static int cached[64] = {0};          // per device ordinal; queried once (the query costs tens of microseconds)
+    int dev = 0;
     hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return stwq::fail(STWQ_EHIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev >= 0 && dev < 64 && cached[dev] > 0) {
+        *out = cached[dev];
+        return STWQ_OK;
+    }
+    int n = 0;
+    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess || n <= 0) return stwq::fail(STWQ_EHIP, "cannot query the compute-unit count: %s", hipGetErrorString(e));
+    if (dev >= 0 && dev < 64) cached[dev] = n;
     *out = n;
     return STWQ_OK;
 }
 
-static int launch_decode(const stwq::DecodeSched& sched, hipStream_t s) {
+static int launch_decode(const stwq::LinearArgs& single, const stwq_linear_problem* problems_dev, int count, long long n_tiles,
+                         const stwq::GroupOrder& order, hipStream_t s) {
     using namespace stwq;
     typedef DecodeCfg C;
     static const int attr = set_ring(linear_decode_kernel, C::kRing);
@@ -631,8 +701,8 @@ static int launch_decode(const stwq::DecodeSched& sched, hipStream_t s) {
     int cus = 0;
     const int rc = compute_units(&cus);
     if (rc != STWQ_OK) return rc;
-    const long long grid = sched.n_tiles < cus ? sched.n_tiles : cus;
-    linear_decode_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(sched);
+    const long long grid = n_tiles < cus ? n_tiles : cus;
+    linear_decode_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(single, problems_dev, count, n_tiles, order);
     return launch_status("linear_decode_kernel");
 }
 
@@ -669,14 +739,10 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
     }
     if (schedule == STWQ_SCHEDULE_DECODE) {
         typedef DecodeCfg C;
-        DecodeSched sched;
-        sched.single = p;
-        sched.problems = nullptr;
-        sched.count = 0;
-        sched.n_tiles = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
-        sched.prefix = nullptr;
-        sched.cursor = 0;
-        return launch_decode(sched, s);
+        const long long n_tiles = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
+        STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
+        static const GroupOrder no_order = {};
+        return launch_decode(p, nullptr, 0, n_tiles, no_order, s);
     }
     if (schedule == STWQ_SCHEDULE_GENERIC) {
         const long long gx = (M + 63) / 64;
@@ -695,13 +761,7 @@ extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int coun
     clear_error();
     STWQ_REQUIRE(problems && problems_dev, "stwq_linear_grouped: null pointer");
     STWQ_REQUIRE(count > 0 && count <= kMaxGroup, "stwq_linear_grouped: count = %d must be in 1 .. %d", count, kMaxGroup);
-    DecodeSched sched;
-    sched.single = LinearArgs{};
-    sched.problems = problems_dev;
-    sched.count = count;
-    sched.n_tiles = 0;
-    sched.prefix = nullptr;
-    sched.cursor = 0;
+    long long n_tiles = 0;
     for (int i = 0; i < count; ++i) {
         const stwq_linear_problem& q = problems[i];
         const int rc = check_linear_args("stwq_linear_grouped", q.q_dev, q.M, q.K, q.N, q.L, q.wq_dev, q.dw_dev, q.wsum_dev,
@@ -709,10 +769,13 @@ extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int coun
         if (rc != STWQ_OK) return rc;
         if (q.K % kBK != 0)
             return fail(STWQ_EUNSUPPORTED, "stwq_linear_grouped: problem %d has K = %d, needs K %% %d == 0", i, q.K, kBK);
-        sched.n_tiles += static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+        n_tiles += static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
     }
-    STWQ_REQUIRE(sched.n_tiles <= 0x7FFFFFFFLL, "stwq_linear_grouped: too many tiles");
-    return launch_decode(sched, static_cast<hipStream_t>(stream));
+    STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear_grouped: too many tiles");
+    GroupOrder order = {};
+    for (int i = 0; i < count; ++i) order.v[i] = static_cast<uint16_t>(i);
+    std::stable_sort(order.v, order.v + count, [&](uint16_t a, uint16_t b) { return problems[a].K > problems[b].K; });
+    return launch_decode(LinearArgs{}, problems_dev, count, n_tiles, order, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,

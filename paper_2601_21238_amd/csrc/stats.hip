@@ -108,6 +108,69 @@ __global__ __launch_bounds__(kStatsThreads) void stats_kernel(
     }
 }
 
+// Channel statistics alone (no position structure needed): a block covers 256 channels (one float4
+// per lane) and a contiguous chunk of rows; its four waves take rows 0,1,2,3 mod 4 of the chunk and
+// merge through LDS, so only one wave per block touches the global buffers (256 x 3 atomics).
+constexpr int kChanThreads = 256;
+constexpr int kChanUnroll = 8;
+
+__global__ __launch_bounds__(kChanThreads) void channel_stats_kernel(
+    const float* __restrict__ x, long long rows, int C, long long rows_per_block,
+    float* __restrict__ ch_min, float* __restrict__ ch_max, float* __restrict__ ch_absmax) {
+    __shared__ float4 s_min[kChanThreads];
+    __shared__ float4 s_max[kChanThreads];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c0 = blockIdx.y * 256 + lane * 4;
+    const bool active = c0 < C;
+    const float inf = __builtin_inff();
+    float4 cmin = make_float4(inf, inf, inf, inf);
+    float4 cmax = make_float4(-inf, -inf, -inf, -inf);
+    const long long r0 = blockIdx.x * rows_per_block;
+    const long long r1 = min(r0 + rows_per_block, rows);
+    if (active) {
+        const float* p = x + c0;
+        long long r = r0 + wave;
+        for (; r + 4 * (kChanUnroll - 1) < r1; r += 4 * kChanUnroll) {
+            float4 v[kChanUnroll];
+#pragma unroll
+            for (int u = 0; u < kChanUnroll; ++u) v[u] = *reinterpret_cast<const float4*>(p + (r + 4 * u) * C);
+#pragma unroll
+            for (int u = 0; u < kChanUnroll; ++u) {
+                cmin.x = fminf(cmin.x, v[u].x); cmax.x = fmaxf(cmax.x, v[u].x);
+                cmin.y = fminf(cmin.y, v[u].y); cmax.y = fmaxf(cmax.y, v[u].y);
+                cmin.z = fminf(cmin.z, v[u].z); cmax.z = fmaxf(cmax.z, v[u].z);
+                cmin.w = fminf(cmin.w, v[u].w); cmax.w = fmaxf(cmax.w, v[u].w);
+            }
+        }
+        for (; r < r1; r += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(p + r * C);
+            cmin.x = fminf(cmin.x, v.x); cmax.x = fmaxf(cmax.x, v.x);
+            cmin.y = fminf(cmin.y, v.y); cmax.y = fmaxf(cmax.y, v.y);
+            cmin.z = fminf(cmin.z, v.z); cmax.z = fmaxf(cmax.z, v.z);
+            cmin.w = fminf(cmin.w, v.w); cmax.w = fmaxf(cmax.w, v.w);
+        }
+    }
+    s_min[tid] = cmin;
+    s_max[tid] = cmax;
+    __syncthreads();
+    if (wave != 0 || !active) return;
+#pragma unroll
+    for (int w = 1; w < kChanThreads / 64; ++w) {
+        const float4 a = s_min[w * 64 + lane], b = s_max[w * 64 + lane];
+        cmin.x = fminf(cmin.x, a.x); cmin.y = fminf(cmin.y, a.y); cmin.z = fminf(cmin.z, a.z); cmin.w = fminf(cmin.w, a.w);
+        cmax.x = fmaxf(cmax.x, b.x); cmax.y = fmaxf(cmax.y, b.y); cmax.z = fmaxf(cmax.z, b.z); cmax.w = fmaxf(cmax.w, b.w);
+    }
+    const float mn[4] = {cmin.x, cmin.y, cmin.z, cmin.w};
+    const float mx[4] = {cmax.x, cmax.y, cmax.z, cmax.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (mn[j] > mx[j]) continue;   // this block saw no row
+        if (ch_min) atomic_min_f32(ch_min + c0 + j, mn[j]);
+        if (ch_max) atomic_max_f32(ch_max + c0 + j, mx[j]);
+        if (ch_absmax) atomic_max_f32(ch_absmax + c0 + j, fmaxf(fabsf(mn[j]), fabsf(mx[j])));
+    }
+}
+
 }  // namespace stwq
 
 extern "C" int stwq_calibrate_stats(const float* x_dev, int64_t rows, int L, int C,
@@ -155,8 +218,18 @@ extern "C" int stwq_calibrate_stats(const float* x_dev, int64_t rows, int L, int
     else if (pos)
         stats_kernel<true, false><<<grid, block, 0, s>>>(x_dev, n_samples, spz, L, C, inv_s_dev, pos_min_dev, pos_max_dev,
                                                          nullptr, nullptr, nullptr);
-    else
-        stats_kernel<false, true><<<grid, block, 0, s>>>(x_dev, n_samples, spz, L, C, nullptr, nullptr, nullptr,
-                                                         ch_min_dev, ch_max_dev, ch_absmax_dev);
+    else {
+        // channel statistics only: about 1024 blocks of 256 channels x a chunk of rows
+        const int cslabs = (C + 255) / 256;
+        long long chunks = 1024 / cslabs;
+        if (chunks < 1) chunks = 1;
+        long long rpb = (rows + chunks - 1) / chunks;
+        if (rpb < 4 * kChanUnroll) rpb = 4 * kChanUnroll;
+        chunks = (rows + rpb - 1) / rpb;
+        STWQ_REQUIRE(cslabs <= 65535, "stwq_calibrate_stats: C = %d is too large", C);
+        channel_stats_kernel<<<dim3(static_cast<unsigned>(chunks), cslabs), dim3(kChanThreads), 0, s>>>(
+            x_dev, rows, C, rpb, ch_min_dev, ch_max_dev, ch_absmax_dev);
+        return launch_status("channel_stats_kernel");
+    }
     return launch_status("stats_kernel");
 }
