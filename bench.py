@@ -29,6 +29,19 @@ INT8_MFMA_PEAK_TOPS = 5033.0     # 256 CUs x 4 SIMDs x 1024 MAC/clk x 2 x 2.4 GH
 HBM_PEAK_GBS = 8000.0
 
 
+def recorded_traffic(key: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this same command (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by the reference copy); None when the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "bench_hbm_traffic_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith(key + ":"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -120,7 +133,8 @@ def decode_step(device, n_iter=30):
             "us": med * 1e6, "gbs": all_bytes / med / 1e9, "weight_gbs": w_bytes / med / 1e9,
             "frac_hbm_peak": all_bytes / med / 1e9 / HBM_PEAK_GBS, "tops": ops / med / 1e12,
             "roofline": {"bound": "hbm", "achieved": all_bytes / mean / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": all_bytes / mean / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "frac": all_bytes / mean / 1e9 / HBM_PEAK_GBS,
+                         "traffic": recorded_traffic("decode_linear_traffic_bytes_per_launch"),
                          "kernel": "stwq::linear_decode_kernel", "avg_launch_us": mean * 1e6},
             "quantize_72_launches_us": qmed * 1e6}
 
@@ -254,6 +268,14 @@ def main() -> int:
                      "frac_hbm_peak": 5.0 * wd.numel() / med / 1e9 / HBM_PEAK_GBS}
     del xc, wd, tmp
     extra["decode"] = decode_step(device)
+    # a plain device-to-device copy of known size: the reference that scales the FETCH_SIZE / WRITE_SIZE counters
+    cal_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=device).normal_()
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    extra["pmc_reference_copy_bytes"] = int(cal_src.numel() * 4)
+    del cal_src, cal_dst
 
     out = {
         "metric": "stwq_w8a8_linear_int8_tops",
@@ -271,7 +293,8 @@ def main() -> int:
         "config": {"workload": "config 2: VAR-d16-shaped block linears (qkv, proj, fc1, fc2), W8A8, M = 32 x 680 = 21760 rows, "
                                "step = quantize + linear for all four"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "frac": achieved / INT8_MFMA_PEAK_TOPS,
+                     "traffic": recorded_traffic("prefill_linear_traffic_bytes_per_launch"),
                      "kernel": "stwq::linear_prefill_kernel", "avg_launch_us": lin_total_avg * 1e6},
         "extra": extra,
     }
