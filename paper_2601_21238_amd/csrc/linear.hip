@@ -420,7 +420,7 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
         offB[ks] = (wm * TJ * 32 + l32) * kBK + pc;
     }
 
-    long long v = blockIdx.x;
+    long long v = sched.first();
     LinearArgs p;
     long long m0;
     int o0;
@@ -524,6 +524,7 @@ struct PatchSched {
     LinearArgs p;
     int tiles_m, tiles_o, patch_o, patch_m;
     long long n_virtual;
+    __device__ __forceinline__ long long first() const { return blockIdx.x; }
     __device__ __forceinline__ bool next(long long& v, LinearArgs& out, long long& m0, int& o0) const {
         for (; v < n_virtual; v += gridDim.x) {
             const int xcd = static_cast<int>(v & 7);
@@ -586,6 +587,13 @@ struct DecodeSched {
     int count;
     long long n_tiles;
     int cursor;                // position in `order` of the previous tile (tiles are visited in increasing order)
+    // Workgroup ids are dealt to the 8 XCDs round-robin by hardware.  The first tile id is a permutation
+    // of the block id that gives each XCD a contiguous run of tiles in every round of gridDim.x tiles:
+    // neighbouring tiles belong to the same linear, so its activation rows are fetched into one L2, not eight.
+    __device__ __forceinline__ long long first() const {
+        const int G = gridDim.x;
+        return (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    }
     __device__ __forceinline__ bool next(long long& v, LinearArgs& out, long long& m0, int& o0) {
         typedef DecodeCfg C;
         if (v >= n_tiles) return false;

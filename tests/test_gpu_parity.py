@@ -98,11 +98,15 @@ CASES = [
     ("tiny",           16,   8,   3,  1,     4,     8,    ("generic",)),
     ("k_tail16",       144,  72,  37, 3,     6,     8,    ("generic",)),
     ("ragged_generic", 160,  200, 37, 5,     6,     6,    ("generic",)),
-    ("ragged_tiles",   256,  328, 131, 5,    6,     8,    ("generic", "prefill", "decode")),
-    ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "prefill", "decode")),
-    ("one_tile",       128,  256, 64, 4,     6,     8,    ("prefill", "decode")),
-    ("one_stage",      64,   136, 9,  15,    6,     8,    ("prefill", "decode")),
+    ("ragged_tiles",   256,  328, 131, 5,    6,     8,    ("generic", "prefill")),
+    ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "prefill")),
+    ("one_tile",       128,  256, 64, 4,     6,     8,    ("prefill",)),
+    ("one_stage",      64,   136, 9,  15,    6,     8,    ("prefill",)),
     ("long_k",         1280, 136, 30, 5,     6,     8,    ("prefill", "decode")),
+    # the streaming (decode) schedule: shortest K it takes, a ragged last K stage, ragged channel and row tiles
+    ("stream_min_k",   704,  264, 53, 3,     6,     8,    ("generic", "decode")),
+    ("stream_ragged",  832,  520, 131, 2,    6,     6,    ("generic", "prefill", "decode")),
+    ("stream_tiles",   768,  776, 300, 1,    4,     8,    ("prefill", "decode")),
 ]
 
 
@@ -145,7 +149,7 @@ def test_config1_full():
 
 @pytest.mark.parametrize("bits", [6, 8])
 def test_edge_inputs(bits):
-    spec = small_spec(K=256, N=264, L=19, batch=15, n_calib=8, a_bits=bits, w_bits=bits)
+    spec = small_spec(K=768, N=264, L=19, batch=15, n_calib=8, a_bits=bits, w_bits=bits)
     w, b, xc, xt = G.make_case(spec)
     pack = G.oracle_pack(spec, xc, w, b)
     layer = G.gpu_layer(spec, xc, w, None, pack["s"])         # no bias
