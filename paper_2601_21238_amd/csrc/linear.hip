@@ -143,7 +143,7 @@ constexpr int kBK = 64;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
-template <int WO_, int WM_, int TI_, int TJ_, int STAGES_>
+template <int WO_, int WM_, int TI_, int TJ_, int STAGES_, int WAVE_STAGE_ = 8192>
 struct TileCfg {
     static constexpr int WO = WO_, WM = WM_, TI = TI_, TJ = TJ_, STAGES = STAGES_;
     static constexpr int kWaves = WO * WM;
@@ -158,7 +158,7 @@ struct TileCfg {
     static constexpr int kLoadsX = kTileM / 16 / kWaves;
     static constexpr int kLoads = kLoadsW + kLoadsX;
     static constexpr int kChunks = TI * 4;                // 16-byte bf16 chunks per staged output row
-    static constexpr int kWaveStage = 8192;               // bytes of LDS one wave stages its output through, per pass
+    static constexpr int kWaveStage = WAVE_STAGE_;        // bytes of LDS one wave stages its output through, per pass
     static constexpr int kJPerPass = kWaveStage / (32 * TI * 64);   // 32-token MFMA tiles staged per pass
     static_assert(kTileO % (16 * kWaves) == 0 && kTileM % (16 * kWaves) == 0, "tile rows must split over the waves");
     static_assert(kJPerPass >= 1 && TJ % kJPerPass == 0, "staging passes must divide the token tiles");
@@ -166,7 +166,10 @@ struct TileCfg {
     static_assert(kLoads * (STAGES - 1) <= 63, "vmcnt is a 6-bit counter");
 };
 typedef TileCfg<2, 4, 4, 2, 4> PrefillCfg;
-typedef TileCfg<2, 2, 2, 2, 8> DecodeCfg;
+// Half as many output channels per tile (wave tile 64 x 64): more LDS traffic per MFMA, but twice
+// the tiles, for shapes whose 256 x 256 tile count leaves most CUs idle in the last round.
+typedef TileCfg<2, 4, 2, 2, 4, 4096> PrefillNarrowCfg;
+typedef TileCfg<2, 2, 2, 2, 4> DecodeCfg;
 
 template <int OFF>
 __device__ __forceinline__ v4i lds_read16(unsigned addr) {
@@ -547,7 +550,6 @@ struct PatchSched {
     }
 };
 
-typedef PatchSched<PrefillCfg> PrefillSched;
 
 // The descriptor is the same for every lane, but it is read with vector loads (the compiler cannot
 // prove that the kernel's own stores leave it alone).  Passing each field through readfirstlane
@@ -615,8 +617,8 @@ struct DecodeSched {
     }
 };
 
-__global__ __launch_bounds__(PrefillCfg::kThreads) void linear_prefill_kernel(PrefillSched sched) {
-    typedef PrefillCfg C;
+template <class C>
+__global__ __launch_bounds__(C::kThreads) void linear_prefill_kernel(PatchSched<C> sched) {
     extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
     __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
     __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
@@ -714,6 +716,33 @@ static int launch_decode(const stwq::LinearArgs& single, const stwq_linear_probl
     return launch_status("linear_decode_kernel");
 }
 
+template <class C>
+static long long prefill_tiles(const stwq::LinearArgs& p) {
+    return static_cast<long long>((p.N + C::kTileO - 1) / C::kTileO) * ((static_cast<long long>(p.M) + C::kTileM - 1) / C::kTileM);
+}
+
+template <class C>
+static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
+    using namespace stwq;
+    static const int attr = set_ring(linear_prefill_kernel<C>, C::kRing);
+    if (attr != STWQ_OK) return attr;
+    PatchSched<C> sched;
+    sched.p = p;
+    sched.tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
+    sched.tiles_m = static_cast<int>((static_cast<long long>(p.M) + C::kTileM - 1) / C::kTileM);
+    // patch of tiles one XCD works on at a time: patch_o x patch_m = 32
+    int patch_o = sched.tiles_o < 4 ? sched.tiles_o : 4;
+    while (32 % patch_o) --patch_o;
+    sched.patch_o = patch_o;
+    sched.patch_m = 32 / patch_o;
+    const long long n_patches = static_cast<long long>((sched.tiles_o + patch_o - 1) / patch_o) *
+                                ((sched.tiles_m + sched.patch_m - 1) / sched.patch_m);
+    sched.n_virtual = ((n_patches + 7) / 8) * 8 * 32;
+    const long long grid = sched.n_virtual < cus ? sched.n_virtual : cus;
+    linear_prefill_kernel<C><<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(sched);
+    return launch_status("linear_prefill_kernel");
+}
+
 static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s) {
     using namespace stwq;
     const long long M = p.M;
@@ -723,27 +752,14 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
     if ((schedule == STWQ_SCHEDULE_PREFILL || schedule == STWQ_SCHEDULE_DECODE) && !tiled_ok)
         return fail(STWQ_EUNSUPPORTED, "stwq_linear: the tiled schedules need K %% %d == 0 (K = %d)", kBK, p.K);
     if (schedule == STWQ_SCHEDULE_PREFILL) {
-        typedef PrefillCfg C;
-        static const int attr = set_ring(linear_prefill_kernel, C::kRing);
-        if (attr != STWQ_OK) return attr;
-        PrefillSched sched;
-        sched.p = p;
-        sched.tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
-        sched.tiles_m = static_cast<int>((M + C::kTileM - 1) / C::kTileM);
-        // patch of tiles one XCD works on at a time: patch_o x patch_m = 32
-        int patch_o = sched.tiles_o < 4 ? sched.tiles_o : 4;
-        while (32 % patch_o) --patch_o;
-        sched.patch_o = patch_o;
-        sched.patch_m = 32 / patch_o;
-        const long long n_patches = static_cast<long long>((sched.tiles_o + patch_o - 1) / patch_o) *
-                                    ((sched.tiles_m + sched.patch_m - 1) / sched.patch_m);
-        sched.n_virtual = ((n_patches + 7) / 8) * 8 * 32;
         int cus = 0;
         const int rc = compute_units(&cus);
         if (rc != STWQ_OK) return rc;
-        const long long grid = sched.n_virtual < cus ? sched.n_virtual : cus;
-        linear_prefill_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(sched);
-        return launch_status("linear_prefill_kernel");
+        // Rounds of one tile per CU; a narrow tile costs a little over half a wide one (measured: 0.55).
+        const long long wide = prefill_tiles<PrefillCfg>(p), narrow = prefill_tiles<PrefillNarrowCfg>(p);
+        const double t_wide = static_cast<double>((wide + cus - 1) / cus);
+        const double t_narrow = 0.55 * static_cast<double>((narrow + cus - 1) / cus);
+        return t_narrow < t_wide ? launch_prefill<PrefillNarrowCfg>(p, cus, s) : launch_prefill<PrefillCfg>(p, cus, s);
     }
     if (schedule == STWQ_SCHEDULE_DECODE) {
         typedef DecodeCfg C;
