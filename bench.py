@@ -101,7 +101,7 @@ def decode_step(device, n_iter=30):
 
     specs = wl.config_linears(4)
     t0 = time.time()
-    problems, keep = [], []
+    problems, keep, qproblems = [], [], []
     for spec in specs:
         w, b = wl.make_weights(spec)
         layer = StwqLinear(spec.N, spec.K, spec.L, spec.a_bits, spec.w_bits, device)
@@ -115,6 +115,8 @@ def decode_step(device, n_iter=30):
         y = torch.empty((spec.M, spec.N), dtype=torch.bfloat16, device=device)
         problems.append(dict(q=q, wq=layer.wq, dw=layer.dw, wsum=layer.wsum, delta=layer.delta[pos:pos + 1],
                              zp=layer.zp[pos:pos + 1], a_bits=spec.a_bits, bias=layer.bias, y=y, L=1))
+        qproblems.append(dict(x=x, L=1, inv_s=layer.inv_s, inv_delta=layer.inv_delta[pos:pos + 1], zp=layer.zp[pos:pos + 1],
+                              a_bits=spec.a_bits, q=q))
         keep.append((layer, x, pos))
         del wd, xc
     torch.cuda.synchronize()
@@ -129,6 +131,14 @@ def decode_step(device, n_iter=30):
         for (layer, x, pos), pr in zip(keep, problems):
             layer.quantize(x, pr["q"], t0=pos)
     qmed, _ = time_launches(quantize_all, 3, 10)
+    qgroup = P.QuantizeGroup(qproblems)
+    qgmed, _ = time_launches(qgroup.run, 3, n_iter)
+
+    def whole_step():
+        qgroup.run()
+        group.run()
+    smed, _ = time_launches(whole_step, 3, n_iter)
+    q_bytes = float(sum(5.0 * s.M * s.K for s in specs))
     return {"workload": "config 4: RAR-XXL-shaped decode step, 72 linears, M = 128, one grouped launch",
             "us": med * 1e6, "gbs": all_bytes / med / 1e9, "weight_gbs": w_bytes / med / 1e9,
             "frac_hbm_peak": all_bytes / med / 1e9 / HBM_PEAK_GBS, "tops": ops / med / 1e12,
@@ -136,7 +146,9 @@ def decode_step(device, n_iter=30):
                          "frac": all_bytes / mean / 1e9 / HBM_PEAK_GBS,
                          "traffic": recorded_traffic("decode_linear_traffic_bytes_per_launch"),
                          "kernel": "stwq::linear_decode_kernel", "avg_launch_us": mean * 1e6},
-            "quantize_72_launches_us": qmed * 1e6}
+            "quantize_72_launches_us": qmed * 1e6, "quantize_grouped_us": qgmed * 1e6,
+            "step_us": smed * 1e6, "step_gbs": (all_bytes + q_bytes) / smed / 1e9,
+            "step_frac_hbm_peak": (all_bytes + q_bytes) / smed / 1e9 / HBM_PEAK_GBS}
 
 
 def cpu_baseline(specs, sample_rows=21760, repeats=3):

@@ -111,6 +111,26 @@ STWQ_API int stwq_quantize_act(const float* x_dev, int64_t M, int K, int L,
                       const float* inv_s_dev, const float* inv_delta_dev, const int32_t* zp_dev,
                       int a_bits, int8_t* q_dev, void* stream);
 
+/* One problem of a grouped activation quantization: the arguments of stwq_quantize_act, all pointers
+ * DEVICE pointers. */
+typedef struct stwq_quantize_problem {
+    const float*   x_dev;
+    const float*   inv_s_dev;     /* may be NULL */
+    const float*   inv_delta_dev;
+    const int32_t* zp_dev;
+    int8_t*        q_dev;
+    int32_t        M, K, L, a_bits;
+} stwq_quantize_problem;
+
+/* Grouped form of stwq_quantize_act (Eq. 1 with the parameters of Section 4.2) for steps made of many
+ * small inputs (a decode step quantizes about a hundred rows in front of every linear): all problems in
+ * ONE launch.  Results are those of stwq_quantize_act on each problem.
+ *   problems      HOST array of count descriptors (read during the call only);
+ *   problems_dev  DEVICE copy of the same descriptors, made by the caller, 8-byte aligned, unchanged until
+ *                 the stream has passed this call;  1 <= count <= 1024, M below 2^31 per problem. */
+STWQ_API int stwq_quantize_act_grouped(const stwq_quantize_problem* problems, int count,
+                                       const stwq_quantize_problem* problems_dev, void* stream);
+
 /* The quantized linear layer: integer product and dequantization (Appendix A.1) into bf16.
  *   acc[m,o] = sum_k q[m,k] * wq[o,k]                                  (int32, exact)
  *   y[m,o]   = bf16( float(acc[m,o] - (zp[t] - off) * wsum[o]) * (delta[t] * dw[o]) + bias[o] )

@@ -19,7 +19,8 @@ _lib = None
 SCHEDULE_AUTO, SCHEDULE_GENERIC, SCHEDULE_PREFILL, SCHEDULE_DECODE = 0, 1, 2, 3
 
 EXPORTS = ("stwq_last_error", "stwq_version", "stwq_calibrate_stats", "stwq_finalize_act_params",
-           "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_linear", "stwq_linear_ex", "stwq_linear_grouped")
+           "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_quantize_act_grouped",
+           "stwq_linear", "stwq_linear_ex", "stwq_linear_grouped")
 
 
 class LinearProblem(C.Structure):
@@ -28,6 +29,12 @@ class LinearProblem(C.Structure):
                 ("delta_dev", C.c_void_p), ("zp_dev", C.c_void_p), ("bias_dev", C.c_void_p), ("y_bf16_dev", C.c_void_p),
                 ("acc_dbg_dev", C.c_void_p), ("M", C.c_int32), ("K", C.c_int32), ("N", C.c_int32), ("L", C.c_int32),
                 ("a_bits", C.c_int32), ("reserved", C.c_int32)]
+
+
+class QuantizeProblem(C.Structure):
+    """Mirror of stwq_quantize_problem."""
+    _fields_ = [("x_dev", C.c_void_p), ("inv_s_dev", C.c_void_p), ("inv_delta_dev", C.c_void_p), ("zp_dev", C.c_void_p),
+                ("q_dev", C.c_void_p), ("M", C.c_int32), ("K", C.c_int32), ("L", C.c_int32), ("a_bits", C.c_int32)]
 
 
 class StwqError(RuntimeError):
@@ -66,6 +73,8 @@ def lib() -> C.CDLL:
     l.gps_fold_weights.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     l.stwq_quantize_act.restype = i32
     l.stwq_quantize_act.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp]
+    l.stwq_quantize_act_grouped.restype = i32
+    l.stwq_quantize_act_grouped.argtypes = [vp, i32, vp, vp]
     l.stwq_linear.restype = i32
     l.stwq_linear.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     l.stwq_linear_ex.restype = i32
@@ -221,3 +230,36 @@ class LinearGroup:
         import torch
         _check(lib().stwq_linear_grouped(C.addressof(self.host), self.count, self.dev.data_ptr(),
                                          torch.cuda.current_stream(self.device).cuda_stream))
+
+
+class QuantizeGroup:
+    """A fixed list of activation-quantization problems prepared once for stwq_quantize_act_grouped."""
+
+    def __init__(self, problems):
+        """problems: list of dicts with the keyword arguments of stwq_quantize_act (x, L, inv_s, inv_delta, zp, a_bits, q).
+        The tensors must stay alive as long as the group is used."""
+        import torch
+        self.count = len(problems)
+        self.host = (QuantizeProblem * self.count)()
+        self._keep = problems
+        dev = None
+        for i, pr in enumerate(problems):
+            x, q = pr["x"], pr["q"]
+            M, K = x.shape
+            L = pr["L"]
+            h = self.host[i]
+            h.x_dev = _dev(x, torch.float32, None, "x")
+            h.inv_s_dev = _dev(pr.get("inv_s"), torch.float32, (K,), "inv_s", True)
+            h.inv_delta_dev = _dev(pr["inv_delta"], torch.float32, (L,), "inv_delta")
+            h.zp_dev = _dev(pr["zp"], torch.int32, (L,), "zp")
+            h.q_dev = _dev(q, torch.int8, (M, K), "q")
+            h.M, h.K, h.L, h.a_bits = M, K, L, pr["a_bits"]
+            dev = x.device
+        raw = np.frombuffer(bytes(self.host), dtype=np.uint8).copy()
+        self.dev = torch.from_numpy(raw).to(dev)
+        self.device = dev
+
+    def run(self) -> None:
+        import torch
+        _check(lib().stwq_quantize_act_grouped(C.addressof(self.host), self.count, self.dev.data_ptr(),
+                                               torch.cuda.current_stream(self.device).cuda_stream))

@@ -11,13 +11,13 @@ constexpr int kQuantThreads = 256;
 constexpr int kQuantRows = 4;
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
+// Rows m0 .. m0 + kQuantRows - 1 of one problem, by one block.
+__device__ __forceinline__ void quantize_rows(
     const float* __restrict__ x, long long M, int K, int L,
     const float* __restrict__ inv_s, const float* __restrict__ inv_delta, const int32_t* __restrict__ zp,
-    float qmax, int off, int8_t* __restrict__ q) {
+    float qmax, int off, int8_t* __restrict__ q, long long m0) {
     const int tid = threadIdx.x;
     const int k4n = K >> 2;
-    const long long m0 = static_cast<long long>(blockIdx.x) * kQuantRows;
 
     float id[kQuantRows], zf[kQuantRows];
     const f4* xr[kQuantRows];
@@ -57,20 +57,71 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     }
 }
 
+__global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
+    const float* __restrict__ x, long long M, int K, int L,
+    const float* __restrict__ inv_s, const float* __restrict__ inv_delta, const int32_t* __restrict__ zp,
+    float qmax, int off, int8_t* __restrict__ q) {
+    quantize_rows(x, M, K, L, inv_s, inv_delta, zp, qmax, off, q, static_cast<long long>(blockIdx.x) * kQuantRows);
+}
+
+// Grouped form: block b belongs to the problem whose run of ceil(M / kQuantRows) blocks contains b.
+// The block counts are fetched by all threads at once (one round trip to memory, not one per
+// problem); the walk over them then runs on LDS.
+constexpr int kQuantMaxGroup = 1024;
+__global__ __launch_bounds__(kQuantThreads) void quantize_grouped_kernel(const stwq_quantize_problem* __restrict__ problems, int count) {
+    __shared__ int nblocks[kQuantMaxGroup];
+    for (int i = threadIdx.x; i < count; i += kQuantThreads) nblocks[i] = (problems[i].M + kQuantRows - 1) / kQuantRows;
+    __syncthreads();
+    int b = blockIdx.x, i = 0;
+    while (i < count && b >= nblocks[i]) b -= nblocks[i++];
+    if (i == count) return;
+    const stwq_quantize_problem& p = problems[i];
+    const float qmax = static_cast<float>((1 << p.a_bits) - 1);
+    quantize_rows(p.x_dev, p.M, p.K, p.L, p.inv_s_dev, p.inv_delta_dev, p.zp_dev, qmax, p.a_bits == 8 ? 128 : 0, p.q_dev,
+                  static_cast<long long>(b) * kQuantRows);
+}
+
 }  // namespace stwq
+
+static int check_quantize_args(const char* who, const float* x_dev, int64_t M, int K, int L, const float* inv_s_dev,
+                               const float* inv_delta_dev, const int32_t* zp_dev, int a_bits, const int8_t* q_dev) {
+    using namespace stwq;
+    STWQ_REQUIRE(x_dev && inv_delta_dev && zp_dev && q_dev, "%s: null pointer", who);
+    STWQ_REQUIRE(M > 0 && K > 0 && L > 0, "%s: M = %lld, K = %d, L = %d must be positive", who, static_cast<long long>(M), K, L);
+    STWQ_REQUIRE(K % 16 == 0, "%s: K = %d must be a multiple of 16", who, K);
+    STWQ_REQUIRE(a_bits == 8 || a_bits == 6, "%s: a_bits = %d, expected 6 or 8", who, a_bits);
+    STWQ_REQUIRE(aligned16(x_dev) && aligned16(q_dev) && (!inv_s_dev || aligned16(inv_s_dev)),
+                 "%s: x_dev, inv_s_dev and q_dev must be 16-byte aligned", who);
+    return STWQ_OK;
+}
+
+extern "C" int stwq_quantize_act_grouped(const stwq_quantize_problem* problems, int count,
+                                         const stwq_quantize_problem* problems_dev, void* stream) {
+    using namespace stwq;
+    clear_error();
+    STWQ_REQUIRE(problems && problems_dev, "stwq_quantize_act_grouped: null pointer");
+    STWQ_REQUIRE(count > 0 && count <= kQuantMaxGroup, "stwq_quantize_act_grouped: count = %d must be in 1 .. %d", count, kQuantMaxGroup);
+    long long blocks = 0;
+    for (int i = 0; i < count; ++i) {
+        const stwq_quantize_problem& p = problems[i];
+        const int rc = check_quantize_args("stwq_quantize_act_grouped", p.x_dev, p.M, p.K, p.L, p.inv_s_dev, p.inv_delta_dev,
+                                           p.zp_dev, p.a_bits, p.q_dev);
+        if (rc != STWQ_OK) return rc;
+        blocks += (static_cast<long long>(p.M) + kQuantRows - 1) / kQuantRows;
+    }
+    STWQ_REQUIRE(blocks <= 0x7FFFFFFFLL, "stwq_quantize_act_grouped: too many rows");
+    quantize_grouped_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kQuantThreads), 0, static_cast<hipStream_t>(stream)>>>(
+        problems_dev, count);
+    return launch_status("quantize_grouped_kernel");
+}
 
 extern "C" int stwq_quantize_act(const float* x_dev, int64_t M, int K, int L,
                                  const float* inv_s_dev, const float* inv_delta_dev, const int32_t* zp_dev,
                                  int a_bits, int8_t* q_dev, void* stream) {
     using namespace stwq;
     clear_error();
-    STWQ_REQUIRE(x_dev && inv_delta_dev && zp_dev && q_dev, "stwq_quantize_act: null pointer");
-    STWQ_REQUIRE(M > 0 && K > 0 && L > 0, "stwq_quantize_act: M = %lld, K = %d, L = %d must be positive",
-                 static_cast<long long>(M), K, L);
-    STWQ_REQUIRE(K % 16 == 0, "stwq_quantize_act: K = %d must be a multiple of 16", K);
-    STWQ_REQUIRE(a_bits == 8 || a_bits == 6, "stwq_quantize_act: a_bits = %d, expected 6 or 8", a_bits);
-    STWQ_REQUIRE(aligned16(x_dev) && aligned16(q_dev) && (!inv_s_dev || aligned16(inv_s_dev)),
-                 "stwq_quantize_act: x_dev, inv_s_dev and q_dev must be 16-byte aligned");
+    const int rc = check_quantize_args("stwq_quantize_act", x_dev, M, K, L, inv_s_dev, inv_delta_dev, zp_dev, a_bits, q_dev);
+    if (rc != STWQ_OK) return rc;
     const long long blocks = (M + kQuantRows - 1) / kQuantRows;
     STWQ_REQUIRE(blocks <= 0x7FFFFFFFLL, "stwq_quantize_act: M = %lld is too large", static_cast<long long>(M));
     const float qmax = static_cast<float>((1 << a_bits) - 1);

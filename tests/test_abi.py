@@ -55,6 +55,9 @@ def test_invalid_arguments_return_einval_without_a_gpu():
     assert b"64" in l.stwq_last_error()
     assert l.stwq_linear_grouped(None, 1, p, None) == EINVAL
     assert l.stwq_linear_grouped(p, 0, p, None) == EINVAL
+    assert l.stwq_quantize_act_grouped(None, 1, p, None) == EINVAL
+    assert l.stwq_quantize_act_grouped(p, 0, p, None) == EINVAL
+    assert l.stwq_quantize_act_grouped(p, 1025, p, None) == EINVAL
 
 
 def test_finalize_host_helper():

@@ -198,7 +198,7 @@ def test_decode_step_grouped():
     """Three RAR-XXL-shaped layers (qkv, fc1, fc2 each) of configuration 4 at full width, M = 128 rows at one
     position per layer, all nine linears in ONE launch; every code, accumulator and output is compared."""
     specs = wl.config_linears(4, blocks=3)
-    packs, layers, problems, refs = [], [], [], []
+    packs, layers, problems, refs, qproblems = [], [], [], [], []
     for spec in specs:
         w, b, xc, xt = G.make_case(spec)
         t0 = wl.decode_position(spec)
@@ -208,12 +208,20 @@ def test_decode_step_grouped():
         q_ref, acc_ref, y_ref = O.forward(pack, xt, t0=t0)
         q = layer.quantize(G.dev(xt), t0=t0)
         assert np.array_equal(G.host(q), q_ref)
+        # the same codes from the grouped quantization launch (checked below)
+        qproblems.append(dict(x=G.dev(xt), L=1, inv_s=layer.inv_s, inv_delta=layer.inv_delta[t0:t0 + 1], zp=layer.zp[t0:t0 + 1],
+                              a_bits=spec.a_bits, q=torch.zeros_like(q), q_ref=q_ref))
         y = torch.zeros((spec.M, spec.N), dtype=torch.bfloat16, device=G.DEV)
         acc = torch.zeros((spec.M, spec.N), dtype=torch.int32, device=G.DEV)
         problems.append(dict(q=q, wq=layer.wq, dw=layer.dw, wsum=layer.wsum, delta=layer.delta[t0:t0 + 1],
                              zp=layer.zp[t0:t0 + 1], a_bits=spec.a_bits, bias=layer.bias, y=y, L=1, acc_dbg=acc))
         refs.append((acc_ref, y_ref, pack))
         layers.append(layer)
+    qgroup = P.QuantizeGroup(qproblems)
+    qgroup.run()
+    torch.cuda.synchronize()
+    for spec, qp in zip(specs, qproblems):
+        assert np.array_equal(G.host(qp["q"]), qp["q_ref"]), f"{spec.name} layer {spec.layer}: grouped codes differ"
     group = P.LinearGroup(problems)
     group.run()
     torch.cuda.synchronize()
