@@ -109,10 +109,12 @@ __global__ __launch_bounds__(kSimpleThreads) void linear_simple_kernel(LinearArg
 // output channels x tokens; each wave owns TI x TJ MFMA tiles.  K is consumed in stages of 64.
 //
 //   prefill: 2 x 4 waves, 4 x 2 MFMA tiles per wave -> 256 x 256 tile, 128 accumulators per lane,
-//            ring of four 32 KB stages (three in flight, 96 KB per CU);
+//            ring of four 32 KB stages (a narrow variant with 2 x 2 MFMA tiles per wave -> 128 x 256
+//            for shapes with too few wide tiles to fill the last round);
 //   decode : 2 x 2 waves, 2 x 2 MFMA tiles per wave -> 128 x 128 tile (all rows of a decode step
-//            against 128 output channels), ring of eight 16 KB stages (seven in flight, 112 KB per
-//            CU): the weight stream is the bottleneck and only bytes in flight hide HBM latency.
+//            against 128 output channels), ring of four 16 KB stages: the weight stream is the
+//            bottleneck, and measured on this part a deeper request queue does not speed it up
+//            (beyond about 32 KB in flight per CU it slows it down).
 //
 // Staging.  Both operand tiles go global -> LDS with direct-to-LDS loads (no register staging).
 // The loaded memory latency here is one to two microseconds and a prefill stage lasts about half
