@@ -151,13 +151,17 @@ STWQ_API int stwq_linear(const int8_t* q_dev, int64_t M, int K, int N, int L,
  * results; the integer part is bit-identical across schedules):
  *   STWQ_SCHEDULE_AUTO     what stwq_linear does;
  *   STWQ_SCHEDULE_GENERIC  one wave per 32 x 32 tile straight from global memory, any valid shape;
- *   STWQ_SCHEDULE_PREFILL  256 x 256 (or 128 x 256) LDS-staged MFMA tiles (MFMA-bound shapes), K a multiple of 64;
+ *   STWQ_SCHEDULE_PREFILL  LDS-staged MFMA tiles (MFMA-bound shapes), K a multiple of 64; 256 x 256 or
+ *                          128 x 256 (channels x rows), whichever needs less time in rounds of one tile per CU;
+ *   STWQ_SCHEDULE_PREFILL_WIDE, STWQ_SCHEDULE_PREFILL_NARROW  the same with the tile named;
  *   STWQ_SCHEDULE_DECODE   128 x 128 tiles (weight-streaming shapes, small M), K a multiple of 64.
  * A schedule that cannot take the shape returns STWQ_EUNSUPPORTED. */
 #define STWQ_SCHEDULE_AUTO    0
 #define STWQ_SCHEDULE_GENERIC 1
 #define STWQ_SCHEDULE_PREFILL 2
 #define STWQ_SCHEDULE_DECODE  3
+#define STWQ_SCHEDULE_PREFILL_WIDE   4
+#define STWQ_SCHEDULE_PREFILL_NARROW 5
 STWQ_API int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,
                    const int8_t* wq_dev, const float* dw_dev, const int32_t* wsum_dev,
                    const float* delta_dev, const int32_t* zp_dev, int a_bits,

@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libstwq.so")
 _lib = None
 
 SCHEDULE_AUTO, SCHEDULE_GENERIC, SCHEDULE_PREFILL, SCHEDULE_DECODE = 0, 1, 2, 3
+SCHEDULE_PREFILL_WIDE, SCHEDULE_PREFILL_NARROW = 4, 5
 
 EXPORTS = ("stwq_last_error", "stwq_version", "stwq_calibrate_stats", "stwq_finalize_act_params",
            "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_quantize_act_grouped",

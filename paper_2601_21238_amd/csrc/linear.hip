@@ -751,17 +751,23 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
     const bool tiled_ok = p.K % kBK == 0;
     if (schedule == STWQ_SCHEDULE_AUTO)
         schedule = !tiled_ok ? STWQ_SCHEDULE_GENERIC : (M > 2 * DecodeCfg::kTileM ? STWQ_SCHEDULE_PREFILL : STWQ_SCHEDULE_DECODE);
-    if ((schedule == STWQ_SCHEDULE_PREFILL || schedule == STWQ_SCHEDULE_DECODE) && !tiled_ok)
+    const bool prefill = schedule == STWQ_SCHEDULE_PREFILL || schedule == STWQ_SCHEDULE_PREFILL_WIDE ||
+                         schedule == STWQ_SCHEDULE_PREFILL_NARROW;
+    if ((prefill || schedule == STWQ_SCHEDULE_DECODE) && !tiled_ok)
         return fail(STWQ_EUNSUPPORTED, "stwq_linear: the tiled schedules need K %% %d == 0 (K = %d)", kBK, p.K);
-    if (schedule == STWQ_SCHEDULE_PREFILL) {
+    if (prefill) {
         int cus = 0;
         const int rc = compute_units(&cus);
         if (rc != STWQ_OK) return rc;
-        // Rounds of one tile per CU; a narrow tile costs a little over half a wide one (measured: 0.55).
-        const long long wide = prefill_tiles<PrefillCfg>(p), narrow = prefill_tiles<PrefillNarrowCfg>(p);
-        const double t_wide = static_cast<double>((wide + cus - 1) / cus);
-        const double t_narrow = 0.55 * static_cast<double>((narrow + cus - 1) / cus);
-        return t_narrow < t_wide ? launch_prefill<PrefillNarrowCfg>(p, cus, s) : launch_prefill<PrefillCfg>(p, cus, s);
+        bool narrow_tile = schedule == STWQ_SCHEDULE_PREFILL_NARROW;
+        if (schedule == STWQ_SCHEDULE_PREFILL) {
+            // Rounds of one tile per CU; a narrow tile costs a little over half a wide one (measured: 0.55).
+            const long long wide = prefill_tiles<PrefillCfg>(p), narrow = prefill_tiles<PrefillNarrowCfg>(p);
+            const double t_wide = static_cast<double>((wide + cus - 1) / cus);
+            const double t_narrow = 0.55 * static_cast<double>((narrow + cus - 1) / cus);
+            narrow_tile = t_narrow < t_wide;
+        }
+        return narrow_tile ? launch_prefill<PrefillNarrowCfg>(p, cus, s) : launch_prefill<PrefillCfg>(p, cus, s);
     }
     if (schedule == STWQ_SCHEDULE_DECODE) {
         typedef DecodeCfg C;

@@ -52,7 +52,10 @@ def test_invalid_arguments_return_einval_without_a_gpu():
     assert l.stwq_linear(p, 4, 32, 16, 2, p, p, p, p, p, 8, None, None, None, None) == EINVAL
     assert l.stwq_linear_ex(p, 4, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 99, None) == EINVAL   # schedule
     assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 2, None) == -2      # prefill needs K % 64
+    assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 4, None) == -2      # so do the named tiles
+    assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 5, None) == -2
     assert b"64" in l.stwq_last_error()
+    assert l.stwq_linear_ex(p, 300, 64, 16, 2, p, p, p, p, p, 8, None, p, None, 6, None) == EINVAL  # unknown schedule
     assert l.stwq_linear_grouped(None, 1, p, None) == EINVAL
     assert l.stwq_linear_grouped(p, 0, p, None) == EINVAL
     assert l.stwq_quantize_act_grouped(None, 1, p, None) == EINVAL

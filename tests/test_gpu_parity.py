@@ -13,7 +13,8 @@ from paper_2601_21238_amd.layer import StwqLinear   # noqa: E402
 import gpu_common as G                       # noqa: E402
 
 F32 = np.float32
-SCHEDULES = {"generic": P.SCHEDULE_GENERIC, "prefill": P.SCHEDULE_PREFILL, "decode": P.SCHEDULE_DECODE}
+SCHEDULES = {"generic": P.SCHEDULE_GENERIC, "prefill": P.SCHEDULE_PREFILL, "decode": P.SCHEDULE_DECODE,
+             "wide": P.SCHEDULE_PREFILL_WIDE, "narrow": P.SCHEDULE_PREFILL_NARROW}
 
 
 def small_spec(**kw):
@@ -98,15 +99,15 @@ CASES = [
     ("tiny",           16,   8,   3,  1,     4,     8,    ("generic",)),
     ("k_tail16",       144,  72,  37, 3,     6,     8,    ("generic",)),
     ("ragged_generic", 160,  200, 37, 5,     6,     6,    ("generic",)),
-    ("ragged_tiles",   256,  328, 131, 5,    6,     8,    ("generic", "prefill")),
-    ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "prefill")),
-    ("one_tile",       128,  256, 64, 4,     6,     8,    ("prefill",)),
-    ("one_stage",      64,   136, 9,  15,    6,     8,    ("prefill",)),
-    ("long_k",         1280, 136, 30, 5,     6,     8,    ("prefill", "decode")),
+    ("ragged_tiles",   256,  328, 131, 5,    6,     8,    ("generic", "wide", "narrow")),
+    ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "wide", "narrow")),
+    ("one_tile",       128,  256, 64, 4,     6,     8,    ("wide", "narrow")),
+    ("one_stage",      64,   136, 9,  15,    6,     8,    ("wide", "narrow")),
+    ("long_k",         1280, 136, 30, 5,     6,     8,    ("wide", "narrow", "prefill", "decode")),
     # the streaming (decode) schedule: shortest K it takes, a ragged last K stage, ragged channel and row tiles
     ("stream_min_k",   704,  264, 53, 3,     6,     8,    ("generic", "decode")),
-    ("stream_ragged",  832,  520, 131, 2,    6,     6,    ("generic", "prefill", "decode")),
-    ("stream_tiles",   768,  776, 300, 1,    4,     8,    ("prefill", "decode")),
+    ("stream_ragged",  832,  520, 131, 2,    6,     6,    ("generic", "wide", "narrow", "decode")),
+    ("stream_tiles",   768,  776, 300, 1,    4,     8,    ("wide", "narrow", "decode")),
 ]
 
 
@@ -135,12 +136,13 @@ def test_config1_full():
     layer = G.gpu_layer(spec, xc, w, b, pack["s"])
     G.check_calibration(layer, pack)
     results = {}
-    for sch in ("generic", "prefill", "decode"):
+    for sch in ("generic", "prefill", "wide", "narrow", "decode"):
         results[sch] = G.check_forward(layer, pack, xt, SCHEDULES[sch], what=f"config1/{sch}")
     # run-to-run determinism and schedule independence of the integer part
     q2, acc2, y2 = G.check_forward(layer, pack, xt, SCHEDULES["prefill"], what="config1/prefill again")
     assert torch.equal(acc2, results["prefill"][1]) and torch.equal(y2, results["prefill"][2])
     assert torch.equal(results["generic"][1], results["prefill"][1]) and torch.equal(results["decode"][1], results["prefill"][1])
+    assert torch.equal(results["wide"][2], results["narrow"][2]) and torch.equal(results["wide"][2], results["prefill"][2])
     assert torch.equal(results["decode"][2], results["prefill"][2])
     # auto picks a schedule and agrees
     y_auto = layer.forward(G.dev(xt))
@@ -162,7 +164,7 @@ def test_edge_inputs(bits):
     x[3] = 1e-42
     x[4, ::2] = np.inf
     x[4, 1::2] = -np.inf
-    for sch in ("generic", "prefill", "decode"):
+    for sch in ("generic", "wide", "narrow", "decode"):
         q, acc, y = G.check_forward(layer, pack, x, SCHEDULES[sch], what=f"edges/{sch}")
         assert not y[0].float().abs().max().item() > 0
     codes = G.host(q).astype(np.int32) + O.store_offset(bits)
