@@ -250,15 +250,16 @@ __device__ __forceinline__ void issue_stage(const TileSrc<C>& t, int stage_idx, 
 
 // One K stage (two MFMA k-steps) of the tile whose stage 0 sits in ring slot `base`.
 template <class C, bool TAIL>
-__device__ __forceinline__ void stage_step(int s, int nk, int base, int8_t* smem, unsigned lds_base, const TileSrc<C>& t,
-                                           const unsigned (&offA)[2], const unsigned (&offB)[2], int wave,
+__device__ __forceinline__ void stage_step(int s, int nk, int base, bool landed, int8_t* smem, unsigned lds_base, const TileSrc<C>& t,
+                                           unsigned offA, unsigned offB, int wave,
                                            v4i (&a0)[C::TI], v4i (&b0)[C::TJ], v4i (&a1)[C::TI], v4i (&b1)[C::TJ],
                                            v16i (&acc)[C::TI][C::TJ]) {
     constexpr int TI = C::TI, TJ = C::TJ;
     const int slot = (base + s) % C::STAGES;
     const unsigned cur = lds_base + slot * C::kStage;
     const unsigned nxt = lds_base + ((slot + 1) % C::STAGES) * C::kStage;
-    read_ops<TI, TJ>(cur + offA[1], cur + C::kOpW + offB[1], a1, b1);
+    // the second k-step's chunk index differs from the first one's in bit 1: address ^ 32 (stage bases are multiples of 64)
+    read_ops<TI, TJ>((cur + offA) ^ 32, (cur + C::kOpW + offB) ^ 32, a1, b1);
     wait_ops<TI + TJ, TI, TJ>(a0, b0);
 #pragma unroll
     for (int i = 0; i < TI; ++i)
@@ -266,12 +267,15 @@ __device__ __forceinline__ void stage_step(int s, int nk, int base, int8_t* smem
         for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);   // the MFMAs above cover the latency of the reads waited for below
     // stage s+1 must have landed; in the steady state the STAGES-2 younger stages may still be in flight
-    if (TAIL) wait_vm<0>();
-    else wait_vm<C::kLoads * (C::STAGES - 2)>();
+    // (`landed`, the same in every lane: the caller knows that it has landed)
+    if (!landed) {
+        if (TAIL) wait_vm<0>();
+        else wait_vm<C::kLoads * (C::STAGES - 2)>();
+    }
     wait_ops<0, TI, TJ>(a1, b1);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    read_ops<TI, TJ>(nxt + offA[0], nxt + C::kOpW + offB[0], a0, b0);
+    read_ops<TI, TJ>(nxt + offA, nxt + C::kOpW + offB, a0, b0);
     // refill the slot every wave has just finished reading, one load group per MFMA group
     const bool do_load = s + C::STAGES < nk;
     int8_t* dst = smem + slot * C::kStage;
@@ -289,113 +293,202 @@ __device__ __forceinline__ void stage_step(int s, int nk, int base, int8_t* smem
     }
 }
 
-// Dequantizes this wave's accumulators and writes them as bf16.  The values are transposed through
-// `stage` (8 KB of LDS private to the wave, 16-byte XOR swizzle) so that the global stores are
-// full row segments of 16 bytes per lane; kPasses passes of JP token tiles each.
-template <class C>
-__device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], int8_t* stage,
-                                         const float* c_dw, const int* c_ws, const float* c_bias, int lane, int wo, int wm) {
-    // On entry the only vector-memory operations in flight are the next tile's first loads.  They
-    // are waited for just before this tile's first store is issued (they have had the arithmetic of
-    // the first pass to land); after that only stores are outstanding, and nothing waits on them.
-    constexpr int TI = C::TI, TJ = C::TJ, JP = C::kJPerPass;
-    constexpr int kRowBytes = TI * 64;
-    const int l32 = lane & 31, hi = lane >> 5;
-    float dt[TJ];
-    int zs[TJ];
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) {
-        int m = static_cast<int>(m0) + wm * TJ * 32 + j * 32 + l32;
-        if (m >= p.M) m = p.M - 1;
-        const int t = m % p.L;
-        dt[j] = p.delta[t];
-        zs[j] = p.off - p.zp[t];            // minus the zero point of the stored codes
-    }
-    typedef __attribute__((address_space(1))) u4 global_u4;
-    constexpr int kRowsPerRead = 64 / C::kChunks;
-    constexpr int kReads = JP * 32 / kRowsPerRead;
-    const int cc = lane % C::kChunks;
-    const int o = o0 + wo * TI * 32 + cc * 8;
-    const bool o_ok = o < p.N;
-    const int cbase = wo * TI * 32 + 4 * hi;
-#pragma unroll
-    for (int pass = 0; pass < TJ / JP; ++pass) {
-        float4 dwv = *reinterpret_cast<const float4*>(c_dw + cbase);
-        int4 wsv = *reinterpret_cast<const int4*>(c_ws + cbase);
-        float4 bv = *reinterpret_cast<const float4*>(c_bias + cbase);
-#pragma unroll
-        for (int c = 0; c < C::kChunks; ++c) {       // c = 4 i + g: channels wo TI 32 + 8 c + 4 hi .. + 3
-            float4 dwn = dwv, bn = bv;
-            int4 wsn = wsv;
-            if (c + 1 < C::kChunks) {                // fetch the next group's constants under this group's arithmetic
-                dwn = *reinterpret_cast<const float4*>(c_dw + cbase + 8 * (c + 1));
-                wsn = *reinterpret_cast<const int4*>(c_ws + cbase + 8 * (c + 1));
-                bn = *reinterpret_cast<const float4*>(c_bias + cbase + 8 * (c + 1));
-            }
-            const int i = c >> 2, g = c & 3;
-#pragma unroll
-            for (int jj = 0; jj < JP; ++jj) {
-                const int j = pass * JP + jj;
-                const int row = jj * 32 + l32;
-                // exact integer part: acc - (z_t - off) wsum[o], one 24-bit multiply-add
-                const float y0 = fmaf(static_cast<float>((__mul24(zs[j], wsv.x) + acc[i][j][4 * g])), dt[j] * dwv.x, bv.x);
-                const float y1 = fmaf(static_cast<float>((__mul24(zs[j], wsv.y) + acc[i][j][4 * g + 1])), dt[j] * dwv.y, bv.y);
-                const float y2 = fmaf(static_cast<float>((__mul24(zs[j], wsv.z) + acc[i][j][4 * g + 2])), dt[j] * dwv.z, bv.z);
-                const float y3 = fmaf(static_cast<float>((__mul24(zs[j], wsv.w) + acc[i][j][4 * g + 3])), dt[j] * dwv.w, bv.w);
-                uint2 out;
-                out.x = pack_bf16(y0, y1);
-                out.y = pack_bf16(y2, y3);
-                *reinterpret_cast<uint2*>(stage + row * kRowBytes + ((c ^ (row & (C::kChunks - 1))) * 16) + hi * 8) = out;
-            }
-            dwv = dwn; wsv = wsn; bv = bn;
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // the same wave wrote and now reads: LDS operations of one wave complete in order
-        const long long mbase = m0 + wm * TJ * 32 + pass * JP * 32 + lane / C::kChunks;
-        global_u4* ybase = (global_u4*)(p.y + mbase * p.N + o);
-        const long long row_step = static_cast<long long>(kRowsPerRead) * p.N / 8;     // in 16-byte units
-        const int8_t* sbase = stage + (lane / C::kChunks) * kRowBytes;
-        if (pass == 0) wait_vm<0>();
-#pragma unroll
-        for (int r0 = 0; r0 < kReads; r0 += 4) {
-            u4 v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int row = (r0 + u) * kRowsPerRead + lane / C::kChunks;
-                v[u] = *reinterpret_cast<const u4*>(sbase + (r0 + u) * kRowsPerRead * kRowBytes + ((cc ^ (row & (C::kChunks - 1))) * 16));
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (o_ok && mbase + (r0 + u) * kRowsPerRead < p.M) ybase[(r0 + u) * row_step] = v[u];
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
+// LDS accesses of the tile boundary by hand.  While direct-to-LDS loads are in flight the compiler
+// answers every LDS access it can see, and every dependency on a loaded register, with vmcnt(0)
+// (after a global_load ... lds it treats the wave as having a flat access outstanding).  At a tile
+// boundary that wait would also cover the output stores just issued, about a microsecond each
+// time; so nothing between a tile's last stage and the next tile's first one is visible to it.
+template <int OFF = 0>
+__device__ __forceinline__ v4i lds_ld16(unsigned addr) {
+    v4i v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int OFF = 0>
+__device__ __forceinline__ int lds_ld4(unsigned addr) {
+    int v;
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+typedef unsigned u2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void lds_st8(unsigned addr, u2 d) {
+    asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(d) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_lgkm() {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+}
+// Pins a value that an asm load produced behind the wait that precedes this call.
+template <class T>
+__device__ __forceinline__ void settle(T& x) {
+    asm volatile("" : "+v"(x));
 }
 
-// Per-output-channel constants of a tile: fetched into registers early (ahead of the tile's operand
-// loads, so that nothing has to wait behind those), written to the LDS table when the table is free.
-struct TileConsts {
-    float dw, bias;
-    int ws;
-};
+// A page of zeros: the source of an absent bias.
+__device__ __attribute__((aligned(256))) const int kZeros[64] = {0};
+
+// Per-tile tables in LDS, two copies (the next tile's arrive while the current tile's are read):
+// per output channel dw, wsum, bias; per token row delta_t and z_t.
 template <class C>
-__device__ __forceinline__ TileConsts load_consts(const LinearArgs& p, int o0, int tid) {
-    static_assert(C::kTileO <= C::kThreads, "one table row per thread");
-    TileConsts c = {0.0f, 0.0f, 0};
-    if (tid < C::kTileO) {
-        const int o = min(o0 + tid, p.N - 1);
-        c.dw = p.dw[o];
-        c.ws = p.wsum[o];
-        c.bias = p.bias ? p.bias[o] : 0.0f;
+struct TileTables {
+    static constexpr int kDw = 0, kWs = C::kTileO * 4, kBias = C::kTileO * 8, kDelta = C::kTileO * 12,
+                         kZp = C::kTileO * 12 + C::kTileM * 4, kBytes = C::kTileO * 12 + C::kTileM * 8;
+    static_assert((C::kTileO & (C::kTileO - 1)) == 0 && (C::kTileM & (C::kTileM - 1)) == 0 && C::kTileO <= C::kThreads &&
+                      C::kTileM <= C::kThreads, "table rows are dealt to threads modulo the table size");
+};
+constexpr int kTableLoads = 5;
+
+// The table loads of a tile: direct-to-LDS like the operands, the same number (kTableLoads) in every
+// wave, issued ahead of the tile's first stage, so that the counted waits for that stage cover them.
+// Waves past the end of a table rewrite entries another wave also writes, with the same values.
+template <class C>
+__device__ __forceinline__ void issue_tables(const LinearArgs& p, long long m0, int o0, int8_t* table, int wave, int lane) {
+    typedef TileTables<C> T;
+    const int e = wave * 64 + lane;
+    const int eo = e % C::kTileO, em = e % C::kTileM;
+    const int o = min(o0 + eo, p.N - 1);
+    const unsigned m = static_cast<unsigned>(min(m0 + em, static_cast<long long>(p.M) - 1));   // M < 2^31
+    const int tok = static_cast<int>(m % static_cast<unsigned>(p.L));
+    int8_t* dst_o = table + ((wave * 64) % C::kTileO) * 4;
+    int8_t* dst_m = table + ((wave * 64) % C::kTileM) * 4;
+    const float* bsrc = p.bias ? p.bias + o : reinterpret_cast<const float*>(kZeros) + lane;
+    __builtin_amdgcn_global_load_lds((global_void*)(p.dw + o), (lds_void*)(dst_o + T::kDw), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)(p.wsum + o), (lds_void*)(dst_o + T::kWs), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)bsrc, (lds_void*)(dst_o + T::kBias), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)(p.delta + tok), (lds_void*)(dst_m + T::kDelta), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)(p.zp + tok), (lds_void*)(dst_m + T::kZp), 4, 0, 0);
+}
+
+// The accumulators of a tile start at the zero-point term of the dequantization,
+//   acc[o, m] = -(z_t - off) * wsum[o]   (|z_t - off| <= 128 and |wsum| < 2^23: one 24-bit multiply),
+// so that the MFMA chain itself leaves the exact corrected integer sum_k (code - z_t) * wq: the
+// multiplies take the place of the moves that would otherwise zero the registers, and the epilogue
+// needs neither wsum nor an integer operation per output.  Int32 accumulation wraps, so partial sums
+// may leave the int32 range as long as the final value fits (K <= 65536 keeps it inside).
+template <class C, int I>
+__device__ __forceinline__ void init_acc_row(v16i (&acc)[C::TI][C::TJ], unsigned ws_addr, const int (&zs)[C::TJ]) {
+    v4i wsv[4];                              // the four channel groups of MFMA tile row I
+#pragma unroll
+    for (int g = 0; g < 4; ++g) wsv[g] = g == 0 ? lds_ld16<32 * (4 * I)>(ws_addr) : g == 1 ? lds_ld16<32 * (4 * I + 1)>(ws_addr)
+                                       : g == 2 ? lds_ld16<32 * (4 * I + 2)>(ws_addr) : lds_ld16<32 * (4 * I + 3)>(ws_addr);
+    wait_lgkm<0>();
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        settle(wsv[g]);
+#pragma unroll
+        for (int j = 0; j < C::TJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[I][j][4 * g + r] = __mul24(zs[j], wsv[g][r]);
     }
-    return c;
+}
+template <class C, int... I>
+__device__ __forceinline__ void init_acc_rows(v16i (&acc)[C::TI][C::TJ], unsigned ws_addr, const int (&zs)[C::TJ],
+                                              std::integer_sequence<int, I...>) {
+    (init_acc_row<C, I>(acc, ws_addr, zs), ...);
 }
 template <class C>
-__device__ __forceinline__ void store_consts(const TileConsts& c, int tid, float* c_dw, int* c_ws, float* c_bias) {
-    if (tid < C::kTileO) {
-        c_dw[tid] = c.dw;
-        c_ws[tid] = c.ws;
-        c_bias[tid] = c.bias;
+__device__ __forceinline__ void init_acc(v16i (&acc)[C::TI][C::TJ], unsigned tab, int off, int lane, int wo, int wm) {
+    typedef TileTables<C> T;
+    const int l32 = lane & 31, hi = lane >> 5;
+    int zs[C::TJ];
+#pragma unroll
+    for (int j = 0; j < C::TJ; ++j) zs[j] = lds_ld4<T::kZp>(tab + (wm * C::TJ * 32 + j * 32 + l32) * 4);
+    wait_lgkm<0>();
+#pragma unroll
+    for (int j = 0; j < C::TJ; ++j) {
+        settle(zs[j]);
+        zs[j] = off - zs[j];                // minus the zero point of the stored codes
+    }
+    init_acc_rows<C>(acc, tab + T::kWs + (wo * C::TI * 32 + 4 * hi) * 4, zs, std::make_integer_sequence<int, C::TI>{});
+}
+
+// Dequantizes this wave's accumulators (already corrected for the zero point, see init_acc) and
+// writes them as bf16.  The values are transposed through `stage` (LDS private to the wave, 16-byte
+// XOR swizzle) so that the global stores are full row segments of 16 bytes per lane; TJ / JP passes
+// of JP token tiles each.  `stage` and `tab` are LDS addresses (this tile's tables).
+template <class C, int CHUNK>
+__device__ __forceinline__ void epilogue_chunk(v16i (&acc)[C::TI][C::TJ], int pass, unsigned cbase, unsigned stage_lane,
+                                               const float (&dt)[C::TJ]) {
+    typedef TileTables<C> T;
+    constexpr int JP = C::kJPerPass, i = CHUNK >> 2, g = CHUNK & 3;
+    // the other wave of this SIMD covers the latency of these reads
+    v4i dwv = lds_ld16<T::kDw + 32 * CHUNK>(cbase), bv = lds_ld16<T::kBias + 32 * CHUNK>(cbase);
+    wait_lgkm<0>();
+    settle(dwv); settle(bv);
+#pragma unroll
+    for (int jj = 0; jj < JP; ++jj) {
+        const int j = pass * JP + jj;
+        const float y0 = fmaf(static_cast<float>(acc[i][j][4 * g]), dt[j] * __int_as_float(dwv[0]), __int_as_float(bv[0]));
+        const float y1 = fmaf(static_cast<float>(acc[i][j][4 * g + 1]), dt[j] * __int_as_float(dwv[1]), __int_as_float(bv[1]));
+        const float y2 = fmaf(static_cast<float>(acc[i][j][4 * g + 2]), dt[j] * __int_as_float(dwv[2]), __int_as_float(bv[2]));
+        const float y3 = fmaf(static_cast<float>(acc[i][j][4 * g + 3]), dt[j] * __int_as_float(dwv[3]), __int_as_float(bv[3]));
+        u2 out = {pack_bf16(y0, y1), pack_bf16(y2, y3)};
+        // chunk c of row r sits at physical chunk c ^ (r & (chunks - 1)); stage_lane holds the lane's row and the
+        // row's own permutation, so the chunk index enters as an XOR
+        lds_st8((stage_lane + jj * 32 * C::TI * 64) ^ (CHUNK * 16), out);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+template <class C, int... CH>
+__device__ __forceinline__ void epilogue_chunks(v16i (&acc)[C::TI][C::TJ], int pass, unsigned cbase, unsigned stage_lane,
+                                                const float (&dt)[C::TJ], std::integer_sequence<int, CH...>) {
+    (epilogue_chunk<C, CH>(acc, pass, cbase, stage_lane, dt), ...);
+}
+
+template <class C>
+__device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], unsigned stage,
+                                         unsigned tab, int lane, int wo, int wm) {
+    // On entry the only vector-memory operations in flight are the next tile's tables and first
+    // stages.  They are waited for just before this tile's first store is issued (they have had the
+    // arithmetic of the first pass to land); after that only stores are outstanding.
+    typedef TileTables<C> T;
+    constexpr int TI = C::TI, TJ = C::TJ, JP = C::kJPerPass, OC = C::kChunks;
+    constexpr int kRowBytes = TI * 64;
+    static_assert(JP * 32 * kRowBytes <= C::kWaveStage && (kRowBytes & (kRowBytes - 1)) == 0, "staging rows");
+    const int l32 = lane & 31, hi = lane >> 5;
+    int dtb[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) dtb[j] = lds_ld4<T::kDelta>(tab + (wm * TJ * 32 + j * 32 + l32) * 4);
+    const unsigned cbase = tab + (wo * TI * 32 + 4 * hi) * 4;      // channels wo TI 32 + 8 c + 4 hi .. + 3 at + 32 c
+    wait_lgkm<0>();
+    float dt[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+        settle(dtb[j]);
+        dt[j] = __int_as_float(dtb[j]);
+    }
+    typedef __attribute__((address_space(1))) u4 global_u4;
+    constexpr int kRowsPerRead = 64 / OC;
+    constexpr int kReads = JP * 32 / kRowsPerRead;
+    const int cc = lane % OC, rr = lane / OC;
+    const int o = o0 + wo * TI * 32 + cc * 8;
+    const bool o_ok = o < p.N;
+    // staging address of this lane's token row (row l32 of each 32-row tile; rows of kRowBytes, a multiple of 16 chunks)
+    const unsigned stage_lane = stage + l32 * kRowBytes + ((l32 & (OC - 1)) * 16) + hi * 8;
+#pragma unroll
+    for (int pass = 0; pass < TJ / JP; ++pass) {
+        epilogue_chunks<C>(acc, pass, cbase, stage_lane, dt, std::make_integer_sequence<int, OC>{});
+        // the same wave wrote and now reads: LDS operations of one wave execute in order
+        const long long mbase = m0 + wm * TJ * 32 + pass * JP * 32 + rr;
+        global_u4* ybase = (global_u4*)(p.y + mbase * p.N + o);
+        const long long row_step = static_cast<long long>(kRowsPerRead) * p.N / 8;     // in 16-byte units
+#pragma unroll
+        for (int r0 = 0; r0 < kReads; r0 += 4) {
+            v4i v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int row = (r0 + u) * kRowsPerRead + rr;
+                v[u] = lds_ld16(stage + row * kRowBytes + ((cc ^ (row & (OC - 1))) * 16));
+            }
+            wait_lgkm<0>();
+            if (pass == 0 && r0 == 0) wait_vm<0>();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                settle(v[u]);
+                if (o_ok && mbase + (r0 + u) * kRowsPerRead < p.M) ybase[(r0 + u) * row_step] = __builtin_bit_cast(u4, v[u]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 }
 
@@ -406,24 +499,22 @@ __device__ __forceinline__ void store_consts(const TileConsts& c, int tid, float
 // and are refilled right after.  So neither the memory latency at the start of a tile nor most of
 // its epilogue leaves the load path idle.
 template <class C, class Sched>
-__device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, float* c_dw, int* c_ws, float* c_bias) {
+__device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem) {
     constexpr int TI = C::TI, TJ = C::TJ, S = C::STAGES, E = 2;
     static_assert(C::kWaves * C::kWaveStage <= E * C::kStage && C::kStage % C::kWaveStage == 0,
                   "output staging must fit two ring slots");
+    static_assert(S - E >= 2, "stages 0 and 1 of a tile are requested ahead of the previous tile's epilogue");
+    int8_t* tables = smem + C::kRing;            // two TileTables, after the ring
     const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>(smem));
+    const unsigned tab_base = lds_base + C::kRing;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int wo = wave % C::WO, wm = wave / C::WO;
 
-    // LDS byte offsets of this lane's MFMA operands for the two k-steps of a stage
-    unsigned offA[2], offB[2];
+    // LDS byte offsets of this lane's MFMA operands for the first k-step of a stage (chunk hi ^ swizzle of its row)
     const int swz = (l32 >> 2) & 3;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const int pc = ((ks * 2 + hi) ^ swz) * 16;
-        offA[ks] = (wo * TI * 32 + l32) * kBK + pc;
-        offB[ks] = (wm * TJ * 32 + l32) * kBK + pc;
-    }
+    const unsigned offA = (wo * TI * 32 + l32) * kBK + ((hi ^ swz) * 16);
+    const unsigned offB = (wm * TJ * 32 + l32) * kBK + ((hi ^ swz) * 16);
 
     long long v = sched.first();
     LinearArgs p;
@@ -434,42 +525,47 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
     tile_sources<C>(p, m0, o0, wave, lane, src);
     int nk = p.K / kBK;
     int base = 0;
+    int tb = 0;                                  // which copy of the tables the current tile uses
     bool first = true;
-    TileConsts consts = load_consts<C>(p, o0, tid);
+    issue_tables<C>(p, m0, o0, tables, wave, lane);
 #pragma unroll
     for (int s = 0; s < S; ++s)
         if (s < nk) issue_stage<C>(src, s, s, smem, wave);
-    store_consts<C>(consts, tid, c_dw, c_ws, c_bias);
 
     while (true) {
         // loop control is the same in every lane; keep it in scalar registers
         nk = __builtin_amdgcn_readfirstlane(nk);
         base = __builtin_amdgcn_readfirstlane(base);
-        v16i acc[TI][TJ];
-#pragma unroll
-        for (int i = 0; i < TI; ++i)
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) acc[i][j] = (v16i){0};
-
-        if (first) {   // stage 0 must have landed; later tiles had theirs waited for in the previous epilogue
+        if (first) {   // tables and stage 0 must have landed; later tiles had theirs waited for in the previous epilogue
             if (nk >= S) wait_vm<C::kLoads * (S - 1)>();
             else wait_vm<0>();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            first = false;
         }
+        v16i acc[TI][TJ];
+        init_acc<C>(acc, tab_base + tb * TileTables<C>::kBytes, p.off, lane, wo, wm);
         v4i a0[TI], b0[TJ], a1[TI], b1[TJ];
         {
-            const unsigned first = lds_base + (base % S) * C::kStage;
-            read_ops<TI, TJ>(first + offA[0], first + C::kOpW + offB[0], a0, b0);
+            const unsigned first_slot = lds_base + (base % S) * C::kStage;
+            read_ops<TI, TJ>(first_slot + offA, first_slot + C::kOpW + offB, a0, b0);
         }
         int s = 0;
         const int n_steady = nk - (S - 1);
-        for (; s < n_steady; ++s) stage_step<C, false>(s, nk, base, smem, lds_base, src, offA, offB, wave, a0, b0, a1, b1, acc);
-        for (; s < nk; ++s) stage_step<C, true>(s, nk, base, smem, lds_base, src, offA, offB, wave, a0, b0, a1, b1, acc);
+        // Stage 1 of a later tile was requested, and waited for, ahead of the previous tile's epilogue: no
+        // wait in its stage 0.  (A counted wait there would also cover that epilogue's stores, which are
+        // younger than stage 1, and would stall until they are acknowledged.)
+        const bool early = !first;
+        first = false;
+        for (; s < n_steady; ++s)
+            stage_step<C, false>(s, nk, base, early && s == 0, smem, lds_base, src, offA, offB, wave, a0, b0, a1, b1, acc);
+        for (; s < nk; ++s)
+            stage_step<C, true>(s, nk, base, early && s == 0, smem, lds_base, src, offA, offB, wave, a0, b0, a1, b1, acc);
         wait_ops<0, TI, TJ>(a0, b0);   // the last prefetch read a slot nobody filled; drain it
 
-        if (p.acc_dbg) {   // raw accumulators for the bit-exact check (debug path, not tuned)
+        if (p.acc_dbg) {   // raw sums of code products for the bit-exact check (debug path, not tuned): the
+                           // accumulators less the zero-point term they started from
+            v16i start[TI][TJ];
+            init_acc<C>(start, tab_base + tb * TileTables<C>::kBytes, p.off, lane, wo, wm);
 #pragma unroll
             for (int j = 0; j < TJ; ++j) {
                 const long long m = m0 + wm * TJ * 32 + j * 32 + l32;
@@ -480,7 +576,8 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
                         const int o4 = o0 + wo * TI * 32 + i * 32 + 8 * g + 4 * hi;
                         if (m < p.M && o4 < p.N)
                             *reinterpret_cast<int4*>(p.acc_dbg + m * p.N + o4) =
-                                make_int4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                                make_int4(acc[i][j][4 * g] - start[i][j][4 * g], acc[i][j][4 * g + 1] - start[i][j][4 * g + 1],
+                                          acc[i][j][4 * g + 2] - start[i][j][4 * g + 2], acc[i][j][4 * g + 3] - start[i][j][4 * g + 3]);
                     }
             }
         }
@@ -494,30 +591,34 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem, flo
         TileSrc<C> srcn;
         int nkn = 0;
         const int b2 = (base + nk) % S;              // ring slot where the next tile's stage 0 goes
-        __syncthreads();                             // every wave is done reading operands; constants table complete
+        // Every wave is done reading operands (its reads were waited for).  Plain barriers here, not
+        // __syncthreads(): its fence waits for every outstanding vector-memory operation, stores included.
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         if (more) {
-            consts = load_consts<C>(pn, o0n, tid);
+            issue_tables<C>(pn, m0n, o0n, tables + (tb ^ 1) * TileTables<C>::kBytes, wave, lane);
             tile_sources<C>(pn, m0n, o0n, wave, lane, srcn);
             nkn = pn.K / kBK;
 #pragma unroll
             for (int q = 0; q < S - E; ++q)
                 if (q < nkn) issue_stage<C>(srcn, q, (b2 + q) % S, smem, wave);
         }
-        // output staging: the two slots that follow in ring order; a wave's 8 KB lies inside one slot
+        // output staging: the two slots that follow in ring order; a wave's share lies inside one slot
         {
             constexpr int waves_per_slot = C::kStage / C::kWaveStage;
             const int slot = (b2 + (S - E) + wave / waves_per_slot) % S;
-            int8_t* stage = smem + slot * C::kStage + (wave % waves_per_slot) * C::kWaveStage;
-            epilogue<C>(p, m0, o0, acc, stage, c_dw, c_ws, c_bias, lane, wo, wm);
+            const unsigned stage = lds_base + slot * C::kStage + (wave % waves_per_slot) * C::kWaveStage;
+            epilogue<C>(p, m0, o0, acc, stage, tab_base + tb * TileTables<C>::kBytes, lane, wo, wm);
         }
         if (!more) break;
-        __syncthreads();                             // staging slots and constants table are free again; every wave's
-                                                     // early loads of the next tile have landed (waited in the epilogue)
-        store_consts<C>(consts, tid, c_dw, c_ws, c_bias);
+        // Staging slots are free again once every wave has read its output back (those reads were waited
+        // for); every wave's early loads of the next tile have landed (waited for in the epilogue).
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
 #pragma unroll
         for (int q = S - E; q < S; ++q)
             if (q < nkn) issue_stage<C>(srcn, q, (b2 + q) % S, smem, wave);
-        p = pn; m0 = m0n; o0 = o0n; src = srcn; nk = nkn; base = b2;
+        p = pn; m0 = m0n; o0 = o0n; src = srcn; nk = nkn; base = b2; tb ^= 1;
     }
 }
 
@@ -621,20 +722,14 @@ struct DecodeSched {
 
 template <class C>
 __global__ __launch_bounds__(C::kThreads) void linear_prefill_kernel(PatchSched<C> sched) {
-    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
-    __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
-    __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
-    __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
-    persistent_tiles<C>(sched, smem, c_dw, c_ws, c_bias);
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // the ring, then two copies of the tile tables
+    persistent_tiles<C>(sched, smem);
 }
 
 __global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(const LinearArgs single, const stwq_linear_problem* problems,
                                                                             int count, long long n_tiles, const GroupOrder order) {
     typedef DecodeCfg C;
-    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
-    __shared__ __attribute__((aligned(16))) float c_dw[C::kTileO];
-    __shared__ __attribute__((aligned(16))) int c_ws[C::kTileO];
-    __shared__ __attribute__((aligned(16))) float c_bias[C::kTileO];
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // the ring, then two copies of the tile tables
     __shared__ int prefix[kMaxGroup + 1];
     if (problems) {
         for (int i = threadIdx.x; i < count; i += C::kThreads) {
@@ -656,7 +751,7 @@ __global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(cons
     sched.count = count;
     sched.n_tiles = n_tiles;
     sched.cursor = 0;
-    persistent_tiles<C>(sched, smem, c_dw, c_ws, c_bias);
+    persistent_tiles<C>(sched, smem);
 }
 
 static int check_linear_args(const char* who, const int8_t* q, int64_t M, int K, int N, int L, const int8_t* wq,
@@ -677,6 +772,12 @@ static int check_linear_args(const char* who, const int8_t* q, int64_t M, int K,
 }
 
 }  // namespace stwq
+
+// Dynamic LDS of a tiled kernel: the ring and two copies of the tile tables.
+template <class C>
+constexpr int tile_lds() {
+    return C::kRing + 2 * stwq::TileTables<C>::kBytes;
+}
 
 template <class Kernel>
 static int set_ring(Kernel kernel, int bytes) {
@@ -708,13 +809,13 @@ static int launch_decode(const stwq::LinearArgs& single, const stwq_linear_probl
                          const stwq::GroupOrder& order, hipStream_t s) {
     using namespace stwq;
     typedef DecodeCfg C;
-    static const int attr = set_ring(linear_decode_kernel, C::kRing);
+    static const int attr = set_ring(linear_decode_kernel, tile_lds<C>());
     if (attr != STWQ_OK) return attr;
     int cus = 0;
     const int rc = compute_units(&cus);
     if (rc != STWQ_OK) return rc;
     const long long grid = n_tiles < cus ? n_tiles : cus;
-    linear_decode_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(single, problems_dev, count, n_tiles, order);
+    linear_decode_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), tile_lds<C>(), s>>>(single, problems_dev, count, n_tiles, order);
     return launch_status("linear_decode_kernel");
 }
 
@@ -726,7 +827,7 @@ static long long prefill_tiles(const stwq::LinearArgs& p) {
 template <class C>
 static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
     using namespace stwq;
-    static const int attr = set_ring(linear_prefill_kernel<C>, C::kRing);
+    static const int attr = set_ring(linear_prefill_kernel<C>, tile_lds<C>());
     if (attr != STWQ_OK) return attr;
     PatchSched<C> sched;
     sched.p = p;
@@ -741,7 +842,7 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
                                 ((sched.tiles_m + sched.patch_m - 1) / sched.patch_m);
     sched.n_virtual = ((n_patches + 7) / 8) * 8 * 32;
     const long long grid = sched.n_virtual < cus ? sched.n_virtual : cus;
-    linear_prefill_kernel<C><<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), C::kRing, s>>>(sched);
+    linear_prefill_kernel<C><<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), tile_lds<C>(), s>>>(sched);
     return launch_status("linear_prefill_kernel");
 }
 
