@@ -98,8 +98,7 @@ __global__ __launch_bounds__(kGpsThreads) void gps_x_kernel(const float* __restr
     const long long r0 = blockIdx.x * rows_per_block;
     const long long r1 = min(r0 + rows_per_block, rows);
     double sx[4] = {0, 0, 0, 0}, sdx[4] = {0, 0, 0, 0};
-    for (long long r = r0; r < r1; ++r) {
-        const float4 v = *reinterpret_cast<const float4*>(x + r * K + c0);
+    auto take = [&](const float4& v) {
         const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -108,7 +107,17 @@ __global__ __launch_bounds__(kGpsThreads) void gps_x_kernel(const float* __restr
             sx[j] += fabs(xd);
             sdx[j] += fabs(xd - delta * (code - z));
         }
+    };
+    // rows in their order (the sums are order dependent in the last bits), four loads in flight per thread
+    long long r = r0;
+    for (; r + 3 < r1; r += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(x + (r + u) * K + c0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) take(v[u]);
     }
+    for (; r < r1; ++r) take(*reinterpret_cast<const float4*>(x + r * K + c0));
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         atomicAdd(w.sum_abs_x + c0 + j, sx[j]);
@@ -246,7 +255,8 @@ extern "C" int gps_solve_scale(const float* x_dev, int64_t rows, int K, const fl
     int rc = launch_status("gps_init_kernel");
     if (rc != STWQ_OK) return rc;
 
-    long long gx = 2048 / slabs;                       // about eight blocks per CU
+    long long gx = 512 / slabs;                        // about two blocks per CU: every thread ends with eight fp64 atomics,
+                                                       // and with many more blocks those, not the reads, set the time
     if (gx < 1) gx = 1;
     if (gx > rows) gx = rows;
     const long long rows_per_block = (rows + gx - 1) / gx;
