@@ -622,37 +622,37 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem) {
     }
 }
 
-// Prefill schedule: virtual workgroup ids are dealt round-robin to the 8 XCDs (each with its own
-// L2) exactly like hardware workgroup ids; the 32 ids an XCD runs together are mapped to a compact
-// patch_m x patch_o patch of tiles so that they share operand rows in that L2.
+// Prefill schedule.  Tiles are numbered so that 32 consecutive ids form a compact patch (8 tile rows
+// x 4 tile columns inside a band of 8 tile rows that runs over all columns; the last band may have
+// fewer rows, never padding), and every id is a real tile: with tile ids dealt to workgroups at
+// stride gridDim.x every workgroup gets the same number of tiles, give or take one.  Hardware deals
+// workgroup ids to the 8 XCDs (each with its own L2) round-robin; the first id is a permutation of
+// the workgroup id that hands each XCD 32 consecutive ids per round, i.e. one patch, whose tiles
+// share operand rows in that L2.
 template <class C>
 struct PatchSched {
     LinearArgs p;
-    int tiles_m, tiles_o, patch_o, patch_m;
-    long long n_virtual;
-    __device__ __forceinline__ long long first() const { return blockIdx.x; }
+    int tiles_m, tiles_o;
+    int n_tiles;
+    static constexpr int kBand = 8;
+    __device__ __forceinline__ long long first() const {
+        const int G = gridDim.x;
+        return (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    }
     __device__ __forceinline__ bool next(long long& v, LinearArgs& out, long long& m0, int& o0) const {
-        for (; v < n_virtual; v += gridDim.x) {
-            const int xcd = static_cast<int>(v & 7);
-            const long long j = v >> 3;
-            const long long patch = (j >> 5) * 8 + xcd;
-            const int idx = static_cast<int>(j & 31);
-            const int npo = (tiles_o + patch_o - 1) / patch_o;
-            const int po = static_cast<int>(patch % npo);
-            const long long pm = patch / npo;
-            const int tile_o = po * patch_o + idx % patch_o;
-            const long long tile_m = pm * patch_m + idx / patch_o;
-            if (tile_o < tiles_o && tile_m < tiles_m) {
-                out = p;
-                m0 = tile_m * C::kTileM;
-                o0 = tile_o * C::kTileO;
-                return true;
-            }
-        }
-        return false;
+        if (v >= n_tiles) return false;
+        const int t = static_cast<int>(v);
+        const int per_band = kBand * tiles_o;
+        const int band = t / per_band;
+        const int r = t - band * per_band;
+        const int rows = min(kBand, tiles_m - band * kBand);      // tile rows of this band
+        const int col = r / rows;
+        out = p;
+        m0 = static_cast<long long>(band * kBand + (r - col * rows)) * C::kTileM;
+        o0 = col * C::kTileO;
+        return true;
     }
 };
-
 
 // The descriptor is the same for every lane, but it is read with vector loads (the compiler cannot
 // prove that the kernel's own stores leave it alone).  Passing each field through readfirstlane
@@ -833,15 +833,10 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
     sched.p = p;
     sched.tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
     sched.tiles_m = static_cast<int>((static_cast<long long>(p.M) + C::kTileM - 1) / C::kTileM);
-    // patch of tiles one XCD works on at a time: patch_o x patch_m = 32
-    int patch_o = sched.tiles_o < 4 ? sched.tiles_o : 4;
-    while (32 % patch_o) --patch_o;
-    sched.patch_o = patch_o;
-    sched.patch_m = 32 / patch_o;
-    const long long n_patches = static_cast<long long>((sched.tiles_o + patch_o - 1) / patch_o) *
-                                ((sched.tiles_m + sched.patch_m - 1) / sched.patch_m);
-    sched.n_virtual = ((n_patches + 7) / 8) * 8 * 32;
-    const long long grid = sched.n_virtual < cus ? sched.n_virtual : cus;
+    const long long n_tiles = static_cast<long long>(sched.tiles_o) * sched.tiles_m;
+    STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
+    sched.n_tiles = static_cast<int>(n_tiles);
+    const long long grid = n_tiles < cus ? n_tiles : cus;
     linear_prefill_kernel<C><<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), tile_lds<C>(), s>>>(sched);
     return launch_status("linear_prefill_kernel");
 }
