@@ -154,7 +154,10 @@ STWQ_API int stwq_linear(const int8_t* q_dev, int64_t M, int K, int N, int L,
  *   STWQ_SCHEDULE_PREFILL  LDS-staged MFMA tiles (MFMA-bound shapes), K a multiple of 64; 256 x 256 or
  *                          128 x 256 (channels x rows), whichever needs less time in rounds of one tile per CU;
  *   STWQ_SCHEDULE_PREFILL_WIDE, STWQ_SCHEDULE_PREFILL_NARROW  the same with the tile named;
- *   STWQ_SCHEDULE_DECODE   128 x 128 tiles (weight-streaming shapes, small M), K a multiple of 64.
+ *   STWQ_SCHEDULE_DECODE   128 x 128 tiles (weight-streaming shapes, small M), K a multiple of 64;
+ *   STWQ_SCHEDULE_STREAM   256 channels x 128 rows per workgroup, weights streamed from global memory straight
+ *                          into registers and only the activations staged in LDS (weight-streaming shapes,
+ *                          small M), K a multiple of 64 and at least 320.
  * A schedule that cannot take the shape returns STWQ_EUNSUPPORTED. */
 #define STWQ_SCHEDULE_AUTO    0
 #define STWQ_SCHEDULE_GENERIC 1
@@ -162,11 +165,27 @@ STWQ_API int stwq_linear(const int8_t* q_dev, int64_t M, int K, int N, int L,
 #define STWQ_SCHEDULE_DECODE  3
 #define STWQ_SCHEDULE_PREFILL_WIDE   4
 #define STWQ_SCHEDULE_PREFILL_NARROW 5
+#define STWQ_SCHEDULE_STREAM  6
 STWQ_API int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,
                    const int8_t* wq_dev, const float* dw_dev, const int32_t* wsum_dev,
                    const float* delta_dev, const int32_t* zp_dev, int a_bits,
                    const float* bias_dev,
                    uint16_t* y_bf16_dev, int32_t* acc_dbg_dev, int schedule, void* stream);
+
+/* Layouts of the quantized weight matrix a grouped launch reads:
+ *   STWQ_LAYOUT_ROWMAJOR  wq [N, K] as gps_fold_weights writes it;
+ *   STWQ_LAYOUT_PANEL32   the output of stwq_pack_weights: blocks of 32 channels x 32 K-bytes, 1 KB each, in
+ *                         MFMA operand order, so that a wave-wide load of the streaming kernel reads
+ *                         consecutive bytes.  Byte (o, k) of wq sits at
+ *                           ((o / 32) (K / 32) + k / 32) 1024 + ((k % 32) / 16 * 32 + o % 32) 16 + k % 16. */
+#define STWQ_LAYOUT_ROWMAJOR 0
+#define STWQ_LAYOUT_PANEL32  1
+
+/* Offline repacking of quantized weights (part of the fold step, Eq. 2) into STWQ_LAYOUT_PANEL32.
+ *   wq_dev [N, K] int8 (16-byte aligned, K a multiple of 32); packed_dev: stwq_packed_weight_bytes(N, K)
+ *   bytes, 16-byte aligned (channels are padded with zeros to a multiple of 32). */
+STWQ_API size_t stwq_packed_weight_bytes(int N, int K);
+STWQ_API int stwq_pack_weights(const int8_t* wq_dev, int N, int K, int8_t* packed_dev, void* stream);
 
 /* One problem of a grouped launch: the arguments of stwq_linear, all pointers DEVICE pointers. */
 typedef struct stwq_linear_problem {
@@ -179,16 +198,19 @@ typedef struct stwq_linear_problem {
     const float*   bias_dev;      /* may be NULL */
     uint16_t*      y_bf16_dev;
     int32_t*       acc_dbg_dev;   /* may be NULL */
-    int32_t        M, K, N, L, a_bits, reserved;
+    int32_t        M, K, N, L, a_bits;
+    int32_t        w_layout;      /* STWQ_LAYOUT_ROWMAJOR, or STWQ_LAYOUT_PANEL32 with wq_dev from stwq_pack_weights */
 } stwq_linear_problem;
 
 /* Grouped form of stwq_linear for steps made of many small independent linears (an autoregressive
  * decode step streams every layer's weights once against about a hundred rows): all problems run
- * in ONE launch with the DECODE schedule, so that launch latency does not hide the weight stream.
+ * in ONE launch (the STREAM schedule when every K allows it, else DECODE), so that launch latency does
+ * not hide the weight stream.
  *   problems      HOST array of count descriptors (read during the call only: validation and grid size);
  *   problems_dev  DEVICE copy of the same count descriptors, made by the caller, 8-byte aligned; the
  *                 kernel reads it, so it must stay unchanged until the stream has passed this call.
- * Every problem must satisfy stwq_linear's rules and have K a multiple of 64; 1 <= count <= 1024. */
+ * Every problem must satisfy stwq_linear's rules and have K a multiple of 64; 1 <= count <= 1024.
+ * Packed weights (w_layout) need K >= 320 in every problem of the group. */
 STWQ_API int stwq_linear_grouped(const stwq_linear_problem* problems, int count,
                                  const stwq_linear_problem* problems_dev, void* stream);
 

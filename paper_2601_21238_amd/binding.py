@@ -17,11 +17,12 @@ _LIB_PATH = os.path.join(_HERE, "libstwq.so")
 _lib = None
 
 SCHEDULE_AUTO, SCHEDULE_GENERIC, SCHEDULE_PREFILL, SCHEDULE_DECODE = 0, 1, 2, 3
-SCHEDULE_PREFILL_WIDE, SCHEDULE_PREFILL_NARROW = 4, 5
+SCHEDULE_PREFILL_WIDE, SCHEDULE_PREFILL_NARROW, SCHEDULE_STREAM = 4, 5, 6
+LAYOUT_ROWMAJOR, LAYOUT_PANEL32 = 0, 1
 
 EXPORTS = ("stwq_last_error", "stwq_version", "stwq_calibrate_stats", "stwq_finalize_act_params",
            "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_quantize_act_grouped",
-           "stwq_linear", "stwq_linear_ex", "stwq_linear_grouped")
+           "stwq_linear", "stwq_linear_ex", "stwq_packed_weight_bytes", "stwq_pack_weights", "stwq_linear_grouped")
 
 
 class LinearProblem(C.Structure):
@@ -29,7 +30,7 @@ class LinearProblem(C.Structure):
     _fields_ = [("q_dev", C.c_void_p), ("wq_dev", C.c_void_p), ("dw_dev", C.c_void_p), ("wsum_dev", C.c_void_p),
                 ("delta_dev", C.c_void_p), ("zp_dev", C.c_void_p), ("bias_dev", C.c_void_p), ("y_bf16_dev", C.c_void_p),
                 ("acc_dbg_dev", C.c_void_p), ("M", C.c_int32), ("K", C.c_int32), ("N", C.c_int32), ("L", C.c_int32),
-                ("a_bits", C.c_int32), ("reserved", C.c_int32)]
+                ("a_bits", C.c_int32), ("w_layout", C.c_int32)]
 
 
 class QuantizeProblem(C.Structure):
@@ -80,6 +81,10 @@ def lib() -> C.CDLL:
     l.stwq_linear.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     l.stwq_linear_ex.restype = i32
     l.stwq_linear_ex.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
+    l.stwq_packed_weight_bytes.restype = C.c_size_t
+    l.stwq_packed_weight_bytes.argtypes = [i32, i32]
+    l.stwq_pack_weights.restype = i32
+    l.stwq_pack_weights.argtypes = [vp, i32, i32, vp, vp]
     l.stwq_linear_grouped.restype = i32
     l.stwq_linear_grouped.argtypes = [vp, i32, vp, vp]
     _lib = l
@@ -195,12 +200,26 @@ def stwq_linear(q, wq, dw, wsum, delta, zp, a_bits: int, bias, y, L: int, acc_db
         _dev(acc_dbg, torch.int32, (M, N), "acc_dbg", True), schedule, _stream(q)))
 
 
+def stwq_packed_weight_bytes(N: int, K: int) -> int:
+    return int(lib().stwq_packed_weight_bytes(N, K))
+
+
+def stwq_pack_weights(wq, packed) -> None:
+    """Repacks wq [N, K] int8 into LAYOUT_PANEL32; packed is an int8 device tensor of stwq_packed_weight_bytes(N, K) bytes."""
+    import torch
+    N, K = wq.shape
+    if packed.dtype != torch.int8 or not packed.is_cuda or not packed.is_contiguous() or packed.numel() != stwq_packed_weight_bytes(N, K):
+        raise ValueError("packed must be a contiguous int8 device tensor of stwq_packed_weight_bytes(N, K) bytes")
+    _check(lib().stwq_pack_weights(_dev(wq, torch.int8, None, "wq"), N, K, packed.data_ptr(), _stream(wq)))
+
+
 class LinearGroup:
     """A fixed list of linear problems prepared once for stwq_linear_grouped (descriptors on host and device)."""
 
     def __init__(self, problems):
         """problems: list of dicts with the keyword arguments of stwq_linear (q, wq, dw, wsum, delta, zp, a_bits,
-        bias, y, L, and optionally acc_dbg).  The tensors must stay alive as long as the group is used."""
+        bias, y, L, and optionally acc_dbg), plus optionally N and w_layout: with w_layout = LAYOUT_PANEL32, wq is the
+        flat output of stwq_pack_weights and N must be given.  The tensors must stay alive as long as the group is used."""
         import torch
         self.count = len(problems)
         self.host = (LinearProblem * self.count)()
@@ -209,11 +228,12 @@ class LinearGroup:
         for i, pr in enumerate(problems):
             q, wq = pr["q"], pr["wq"]
             M, K = q.shape
-            N = wq.shape[0]
+            layout = pr.get("w_layout", LAYOUT_ROWMAJOR)
+            N = pr["N"] if layout == LAYOUT_PANEL32 else wq.shape[0]
             L = pr["L"]
             h = self.host[i]
             h.q_dev = _dev(q, torch.int8, None, "q")
-            h.wq_dev = _dev(wq, torch.int8, (N, K), "wq")
+            h.wq_dev = _dev(wq, torch.int8, (stwq_packed_weight_bytes(N, K),) if layout == LAYOUT_PANEL32 else (N, K), "wq")
             h.dw_dev = _dev(pr["dw"], torch.float32, (N,), "dw")
             h.wsum_dev = _dev(pr["wsum"], torch.int32, (N,), "wsum")
             h.delta_dev = _dev(pr["delta"], torch.float32, (L,), "delta")
@@ -221,7 +241,7 @@ class LinearGroup:
             h.bias_dev = _dev(pr.get("bias"), torch.float32, (N,), "bias", True)
             h.y_bf16_dev = _dev(pr["y"], torch.bfloat16, (M, N), "y")
             h.acc_dbg_dev = _dev(pr.get("acc_dbg"), torch.int32, (M, N), "acc_dbg", True)
-            h.M, h.K, h.N, h.L, h.a_bits, h.reserved = M, K, N, L, pr["a_bits"], 0
+            h.M, h.K, h.N, h.L, h.a_bits, h.w_layout = M, K, N, L, pr["a_bits"], layout
             dev = q.device
         raw = np.frombuffer(bytes(self.host), dtype=np.uint8).copy()
         self.dev = torch.from_numpy(raw).to(dev)

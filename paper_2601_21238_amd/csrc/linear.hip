@@ -435,12 +435,13 @@ __device__ __forceinline__ void epilogue_chunks(v16i (&acc)[C::TI][C::TJ], int p
     (epilogue_chunk<C, CH>(acc, pass, cbase, stage_lane, dt), ...);
 }
 
-template <class C>
+template <class C, bool DRAIN = true>
 __device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], unsigned stage,
                                          unsigned tab, int lane, int wo, int wm) {
-    // On entry the only vector-memory operations in flight are the next tile's tables and first
-    // stages.  They are waited for just before this tile's first store is issued (they have had the
-    // arithmetic of the first pass to land); after that only stores are outstanding.
+    // DRAIN (the tiled kernels): on entry the only vector-memory operations in flight are the next
+    // tile's tables and first stages.  They are waited for just before this tile's first store is
+    // issued (they have had the arithmetic of the first pass to land); after that only stores are
+    // outstanding.  The streaming kernel keeps its loads in flight across the epilogue.
     typedef TileTables<C> T;
     constexpr int TI = C::TI, TJ = C::TJ, JP = C::kJPerPass, OC = C::kChunks;
     constexpr int kRowBytes = TI * 64;
@@ -481,7 +482,7 @@ __device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int 
                 v[u] = lds_ld16(stage + row * kRowBytes + ((cc ^ (row & (OC - 1))) * 16));
             }
             wait_lgkm<0>();
-            if (pass == 0 && r0 == 0) wait_vm<0>();
+            if (DRAIN && pass == 0 && r0 == 0) wait_vm<0>();
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 settle(v[u]);
@@ -754,6 +755,494 @@ __global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(cons
     persistent_tiles<C>(sched, smem);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Streaming kernel for the decode regime (about a hundred rows, every weight byte read once).
+//
+// The tiled decode kernel above sends both operands through LDS, and for a 128-row problem that is
+// what bounds it: per 16 KB of weights the LDS port moves 32 KB of direct-to-LDS writes and 64 KB of
+// operand reads, about as long as HBM needs to deliver those 16 KB.  This kernel halves the traffic
+// through LDS per weight byte twice over:
+//   * WEIGHTS go from global memory straight into registers, already in MFMA A-operand form; each
+//     of the 4 waves reads only its own 64 output channels, so no weight byte passes through LDS
+//     or is fetched twice.  With one wave per SIMD the register file holds D stages of them.
+//   * Each wave multiplies its 64 channels against ALL 128 rows (2 x 4 MFMA tiles, 128
+//     accumulators), so one B operand read from LDS serves two MFMAs.
+//   * ACTIVATIONS are shared by the four waves and go through an LDS ring of D stages of 128 bytes
+//     of K per row (16 KB per stage), filled by direct-to-LDS BUFFER loads.  The buffer form
+//     matters: after a global_load ... lds the compiler's wait-count pass treats the wave as
+//     having a flat access in flight and answers every later dependency on a loaded register with
+//     vmcnt(0), which would drain the weight stream at every use; after buffer_load ... lds it
+//     keeps exact counts.  The buffer's range check also makes rows past the end of the matrix
+//     and the 64 bytes a row may be read past its end harmless (the matching weight k-steps are
+//     zero).
+//   * Both streams are ONE sequence of stages that runs across tile boundaries: stage g + D is
+//     requested while stage g is consumed, whichever tile it belongs to; past the end of the tile
+//     list the requests repeat valid addresses, so that every stage issues the same memory
+//     operations in the same order.  The waits for weight registers are the compiler's; the waits
+//     for the ring are counted by hand (operations complete in issue order), and extra operations
+//     in between (a tile's table loads, output stores) only make them stricter.  The stage loop
+//     leaves only at its end: an exit from the middle of the unrolled body would give the compiler
+//     a path from a stage's loads straight back to their uses, and it would wait for them with
+//     vmcnt near zero.
+//   * Weights may be row-major [N, K] or in the panel layout of stwq_pack_weights, in which a
+//     wave-wide load reads 1 KB of consecutive bytes.  Both are "lane base + k-step x stride".
+// Tile tables, accumulator start, epilogue arithmetic and tile order are those of the tiled kernels.
+// ------------------------------------------------------------------------------------------------
+template <int D_>
+struct StreamCfg {
+    static constexpr int D = D_;                          // stages in flight = ring slots = weight register sets
+    static constexpr int BK = 128, kKS = BK / 32;         // bytes of K per stage; MFMA k-steps per stage
+    static constexpr int kWaves = 4, kThreads = 256;
+    static constexpr int TI = 2, TJ = 4;                  // MFMA tiles per wave: 64 channels x 128 rows
+    static constexpr int kTileO = kWaves * TI * 32, kTileM = TJ * 32;
+    static constexpr int kChunks = TI * 4;                // 16-byte bf16 chunks per staged output row
+    static constexpr int kOpX = kTileM * BK;              // one ring slot
+    static constexpr int kRing = D * kOpX;
+    static constexpr int kLoadsX = kOpX / 1024 / kWaves;  // direct-to-LDS loads per wave and stage (8 rows each)
+    static constexpr int kLoadsW = kKS * TI;              // weight loads per wave and stage
+    static constexpr int kOps = kLoadsX + kLoadsW;
+    static constexpr int kWaveStage = 32 * TI * 64;       // output staging: 32 rows x 64 channels of bf16
+    static constexpr int kJPerPass = 1;
+    static constexpr int kOffStaging = kRing, kOffTables = kRing + kWaves * kWaveStage;
+    // Ring wait in the steady state: operations issued after the awaited stage's ring loads.  A stage is
+    // requested as W(k-steps 0 .. 2) | X x kLoadsX | W(k-step 3); awaited are the X loads of the stage after the
+    // current one.  One less than the count, in case the compiler swaps a weight load with a ring load.
+    static constexpr int kWaitSteady = TI + kOps * (D - 2) + TI * (kKS - 1) - 1;
+    static constexpr int kWaitFirst = TI + kOps * (D - 1) - 1;
+    static_assert(D >= 2 && kWaitFirst <= 63, "vmcnt is a 6-bit counter");
+};
+typedef StreamCfg<3> StreamDecodeCfg;
+
+typedef __attribute__((address_space(1))) v4i global_v4i;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ int lds_ld2_now(unsigned addr) {      // unsigned 16 bits; value valid on return
+    int v;
+    asm volatile("ds_read_u16 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr));
+    return v;
+}
+__device__ __forceinline__ int lds_ld4_now(unsigned addr) {      // value valid on return
+    int v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr));
+    return v;
+}
+
+template <class C>
+struct StreamTile {
+    LinearArgs p;
+    long long m0;
+    int o0;
+    int nk;              // K stages, the last possibly ragged
+    int tail_ks;         // valid k-steps in the last stage; 0 = all
+    int kstep_stride;    // bytes between consecutive k-steps of a lane's weight operand
+    const int8_t* w[C::TI];   // this lane's weight operands of k-step 0
+    const int8_t* xbase; // first activation row of the tile; the ring loads address it as a raw buffer
+    unsigned xbytes;     // bytes from xbase to the end of the activation matrix (saturated): rows past the end
+                         // of the matrix fail the buffer's range check and are not read
+    unsigned xoff;       // this lane's byte offset from xbase at K position 0 in the first ring load
+};
+
+// Row and logical 16-byte chunk behind lane `lane` of this wave's u-th ring load (8 rows of 128 bytes;
+// the chunks of row r are permuted by chunk ^ ((r >> 1) & 7), applied on the global side).
+template <class C>
+__device__ __forceinline__ int ring_row(int u, int wave, int lane) {
+    return (u * C::kWaves + wave) * 8 + lane / 8;
+}
+__device__ __forceinline__ int ring_chunk(int row, int lane) {
+    return (lane % 8) ^ ((row >> 1) & 7);
+}
+
+template <class C>
+__device__ __forceinline__ void stream_prepare(StreamTile<C>& t, int w_layout, int wave, int lane) {
+    asm volatile("" : "+v"(lane));   // lane-dependent addresses are recomputed per call, not kept in registers across the K loop
+    const LinearArgs& p = t.p;
+    const int l32 = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < C::TI; ++i) {
+        if (w_layout == STWQ_LAYOUT_PANEL32) {
+            // panel (32 channels) x k-step (32 bytes) blocks of 1 KB, a lane's 16 bytes at 16 * lane
+            const size_t panel = static_cast<size_t>(min(t.o0 / 32 + wave * C::TI + i, (p.N + 31) / 32 - 1));   // past N: any valid panel
+            t.w[i] = p.wq + panel * (static_cast<size_t>(p.K / 32) * 1024) + lane * 16;
+        } else {
+            t.w[i] = p.wq + static_cast<size_t>(min(t.o0 + (wave * C::TI + i) * 32 + l32, p.N - 1)) * p.K + hi * 16;
+        }
+    }
+    t.kstep_stride = w_layout == STWQ_LAYOUT_PANEL32 ? 1024 : 32;
+    t.xbase = p.q + static_cast<size_t>(t.m0) * p.K;
+    const unsigned long long rest = static_cast<unsigned long long>(p.M - t.m0) * p.K;
+    t.xbytes = rest < 0xFFFFFFFFull ? static_cast<unsigned>(rest) : 0xFFFFFFFFu;
+    {   // ring load u covers rows 32 u + 8 wave + lane / 8: the same chunk permutation for every u
+        const int r = ring_row<C>(0, wave, lane);
+        t.xoff = static_cast<unsigned>(r) * p.K + ring_chunk(r, lane) * 16;
+    }
+    t.nk = (p.K + C::BK - 1) / C::BK;
+    t.tail_ks = (p.K % C::BK) / 32;
+}
+
+// The table loads of a tile, into one copy of TileTables (buffer form of issue_tables).
+template <class C>
+__device__ __forceinline__ void stream_tables(const StreamTile<C>& t, int8_t* table, int wave, int lane) {
+    typedef TileTables<C> T;
+    asm volatile("" : "+v"(lane));
+    const LinearArgs& p = t.p;
+    const int e = wave * 64 + lane;
+    const int eo = e % C::kTileO, em = e % C::kTileM;
+    const int o = min(t.o0 + eo, p.N - 1);
+    const unsigned m = static_cast<unsigned>(min(t.m0 + em, static_cast<long long>(p.M) - 1));   // M < 2^31
+    const int tok = static_cast<int>(m % static_cast<unsigned>(p.L));
+    int8_t* dst_o = table + ((wave * 64) % C::kTileO) * 4;
+    int8_t* dst_m = table + ((wave * 64) % C::kTileM) * 4;
+    const unsigned nb = static_cast<unsigned>(p.N) * 4, lb = static_cast<unsigned>(p.L) * 4;
+    const bool has_bias = p.bias != nullptr;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(raw_buffer(p.dw, nb), (lds_void*)(dst_o + T::kDw), 4, o * 4, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(raw_buffer(p.wsum, nb), (lds_void*)(dst_o + T::kWs), 4, o * 4, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(raw_buffer(has_bias ? static_cast<const void*>(p.bias) : kZeros, has_bias ? nb : 256u),
+                                             (lds_void*)(dst_o + T::kBias), 4, has_bias ? o * 4 : lane * 4, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(raw_buffer(p.delta, lb), (lds_void*)(dst_m + T::kDelta), 4, tok * 4, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(raw_buffer(p.zp, lb), (lds_void*)(dst_m + T::kZp), 4, tok * 4, 0, 0, 0);
+}
+
+// Where the stage requested now comes from: a tile and a stage in it, or nowhere (past the tile list).
+template <class C>
+struct StreamSrc {
+    const int8_t* w[C::TI];
+    const int8_t* xbase;
+    unsigned xbytes;
+    unsigned xoff;
+    int K;
+    int kstep;           // first k-step of the stage, counted from the tile's k-step 0
+    int kstep_stride;
+    int valid_ks;        // k-steps of this stage that exist (C::kKS except in a ragged last stage; 0 = none)
+};
+template <class C>
+__device__ __forceinline__ StreamSrc<C> stream_source(const StreamTile<C>& cur, const StreamTile<C>& nxt, bool more, bool done, int t) {
+    StreamSrc<C> r;
+    const bool in_cur = !done && t < cur.nk;
+    const int tt = in_cur ? t : t - cur.nk;
+    const int nk = in_cur ? cur.nk : nxt.nk;
+    const int tail = in_cur ? cur.tail_ks : nxt.tail_ks;
+    const bool real = in_cur || more;             // otherwise: past the end of the tile list
+#pragma unroll
+    for (int i = 0; i < C::TI; ++i) r.w[i] = in_cur ? cur.w[i] : nxt.w[i];
+    r.xbase = (in_cur || !more) ? cur.xbase : nxt.xbase;
+    r.xbytes = (in_cur || !more) ? cur.xbytes : nxt.xbytes;
+    r.xoff = (in_cur || !more) ? cur.xoff : nxt.xoff;
+    r.K = (in_cur || !more) ? cur.p.K : nxt.p.K;
+    r.kstep = real ? tt * C::kKS : 0;             // nobody consumes an unreal stage: its ring loads re-read the tile's first bytes
+    r.kstep_stride = in_cur ? cur.kstep_stride : nxt.kstep_stride;
+    r.valid_ks = real ? ((tail != 0 && tt == nk - 1) ? tail : C::kKS) : 0;
+    return r;
+}
+// The weight operand i of k-step ks of the requested stage (zeros where the stage has no such k-step).
+template <class C>
+__device__ __forceinline__ v4i stream_load_w(const StreamSrc<C>& r, int ks, int i) {
+    const int8_t* a = r.w[i] + static_cast<long long>(r.kstep + ks) * r.kstep_stride;
+    if (ks >= r.valid_ks) a = reinterpret_cast<const int8_t*>(kZeros);
+    return *(const global_v4i*)a;                 // a global (not flat) load, tracked by the compiler
+}
+// The ring loads of the requested stage into the slot at `slot`.
+template <class C>
+__device__ __forceinline__ void stream_load_x(const StreamSrc<C>& r, int8_t* slot, int wave) {
+    // the whole offset goes into the per-lane operand: the range check does not cover the scalar offset
+    const __amdgpu_buffer_rsrc_t rs = raw_buffer(r.xbase, r.xbytes);
+#pragma unroll
+    for (int u = 0; u < C::kLoadsX; ++u)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(slot + (u * C::kWaves + wave) * 1024), 16,
+                                                 r.xoff + static_cast<unsigned>(u * C::kWaves * 8 * r.K + r.kstep * 32), 0, 0, 0);
+}
+
+template <int... J>
+__device__ __forceinline__ void stream_read_b(unsigned addr, v4i (&b)[sizeof...(J)], std::integer_sequence<int, J...>) {
+    ((b[J] = lds_read16<J * 32 * 128>(addr)), ...);
+}
+
+// Epilogue of the streaming kernel (the arithmetic of `epilogue`).  One wave per SIMD: nobody else
+// covers an LDS round trip, so all per-channel constants of the wave's 64 channels are fetched with a
+// single wait and kept for the four passes (one per 32-row MFMA tile).
+template <class C, int... CH>
+__device__ __forceinline__ void stream_consts(unsigned cbase, v4i (&dwv)[sizeof...(CH)], v4i (&bv)[sizeof...(CH)],
+                                              std::integer_sequence<int, CH...>) {
+    typedef TileTables<C> T;
+    ((dwv[CH] = lds_ld16<T::kDw + 32 * CH>(cbase)), ...);
+    ((bv[CH] = lds_ld16<T::kBias + 32 * CH>(cbase)), ...);
+}
+template <class C>
+__device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], unsigned stage,
+                                                unsigned tab, int lane, int wave) {
+    typedef TileTables<C> T;
+    asm volatile("" : "+v"(lane));   // lane-dependent addresses are recomputed per call, not kept in registers across the K loop
+    constexpr int TI = C::TI, TJ = C::TJ, OC = C::kChunks;
+    constexpr int kRowBytes = TI * 64;
+    const int l32 = lane & 31, hi = lane >> 5;
+    int dtb[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) dtb[j] = lds_ld4<T::kDelta>(tab + (j * 32 + l32) * 4);
+    v4i dwv[OC], bv[OC];
+    stream_consts<C>(tab + (wave * TI * 32 + 4 * hi) * 4, dwv, bv, std::make_integer_sequence<int, OC>{});
+    wait_lgkm<0>();
+    float dt[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+        settle(dtb[j]);
+        dt[j] = __int_as_float(dtb[j]);
+    }
+#pragma unroll
+    for (int c = 0; c < OC; ++c) { settle(dwv[c]); settle(bv[c]); }
+    typedef __attribute__((address_space(1))) u4 global_u4;
+    constexpr int kRowsPerRead = 64 / OC, kReads = 32 / kRowsPerRead;
+    const int cc = lane % OC, rr = lane / OC;
+    const int o = o0 + wave * TI * 32 + cc * 8;
+    const bool o_ok = o < p.N;
+    const unsigned stage_lane = stage + l32 * kRowBytes + ((l32 & (OC - 1)) * 16) + hi * 8;
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+#pragma unroll
+        for (int c = 0; c < OC; ++c) {           // c = 4 i + g: channels (wave TI + i) 32 + 8 g + 4 hi .. + 3
+            const int i = c >> 2, g = c & 3;
+            const float y0 = fmaf(static_cast<float>(acc[i][j][4 * g]), dt[j] * __int_as_float(dwv[c][0]), __int_as_float(bv[c][0]));
+            const float y1 = fmaf(static_cast<float>(acc[i][j][4 * g + 1]), dt[j] * __int_as_float(dwv[c][1]), __int_as_float(bv[c][1]));
+            const float y2 = fmaf(static_cast<float>(acc[i][j][4 * g + 2]), dt[j] * __int_as_float(dwv[c][2]), __int_as_float(bv[c][2]));
+            const float y3 = fmaf(static_cast<float>(acc[i][j][4 * g + 3]), dt[j] * __int_as_float(dwv[c][3]), __int_as_float(bv[c][3]));
+            u2 out = {pack_bf16(y0, y1), pack_bf16(y2, y3)};
+            lds_st8(stage_lane ^ (c * 16), out);
+        }
+        // the same wave wrote and now reads: LDS operations of one wave execute in order
+        v4i v[kReads];
+#pragma unroll
+        for (int u = 0; u < kReads; ++u) {
+            const int row = u * kRowsPerRead + rr;
+            v[u] = lds_ld16(stage + row * kRowBytes + ((cc ^ (row & (OC - 1))) * 16));
+        }
+        wait_lgkm<0>();
+        const long long mbase = m0 + j * 32 + rr;
+        global_u4* ybase = (global_u4*)(p.y + mbase * p.N + o);
+        const long long row_step = static_cast<long long>(kRowsPerRead) * p.N / 8;     // in 16-byte units
+#pragma unroll
+        for (int u = 0; u < kReads; ++u) {
+            settle(v[u]);
+            if (o_ok && mbase + u * kRowsPerRead < p.M) ybase[u * row_step] = __builtin_bit_cast(u4, v[u]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Decode schedule for the streaming kernel: tile v of the concatenated tile lists of the problems in
+// processing order (channel tiles fastest within a problem).
+template <class C>
+struct StreamSched {
+    LinearArgs single;
+    const stwq_linear_problem* problems;
+    unsigned prefix;           // LDS address of count + 1 running tile counts, problems in processing order
+    unsigned order;            // LDS address of the problem index (16 bits) at each position of that order
+    long long n_tiles;
+    int cursor;                // position in the order of the previous tile (tiles are visited in increasing order)
+    __device__ __forceinline__ bool next(long long v, StreamTile<C>& t, int wave, int lane) {
+        if (v >= n_tiles) return false;
+        int tile = static_cast<int>(v);
+        int layout = STWQ_LAYOUT_ROWMAJOR;
+        if (problems) {
+            int i = cursor;
+            while (tile >= __builtin_amdgcn_readfirstlane(lds_ld4_now(prefix + 4 * (i + 1)))) ++i;   // scalar condition: a uniform loop
+            cursor = i;
+            tile -= __builtin_amdgcn_readfirstlane(lds_ld4_now(prefix + 4 * i));
+            const stwq_linear_problem& q = problems[__builtin_amdgcn_readfirstlane(lds_ld2_now(order + 2 * i))];
+            t.p = args_of(q);
+            layout = __builtin_amdgcn_readfirstlane(q.w_layout);
+        } else {
+            t.p = single;
+        }
+        const int tiles_o = (t.p.N + C::kTileO - 1) / C::kTileO;
+        const int tile_m = tile / tiles_o;
+        t.m0 = static_cast<long long>(tile_m) * C::kTileM;
+        t.o0 = (tile - tile_m * tiles_o) * C::kTileO;
+        stream_prepare<C>(t, layout, wave, lane);
+        return true;
+    }
+};
+
+template <class C, class Sched>
+__device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
+    constexpr int TI = C::TI, TJ = C::TJ, D = C::D, KS = C::kKS;
+    typedef TileTables<C> T;
+    const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>(smem));
+    const unsigned tab_base = lds_base + C::kOffTables;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+
+    // LDS byte offset (from the start of a ring slot) of this lane's B operand for k-step 0; k-step ks
+    // sits at this offset ^ 32 ks (the chunk index is (2 ks + hi) ^ swizzle and 2 ks has no low bit)
+    const unsigned offB = l32 * C::BK + ((hi ^ ((l32 >> 1) & 7)) * 16);
+
+    // Tile ids of this workgroup: stride gridDim.x, starting at a permutation of the block id that
+    // gives the 8 XCDs contiguous runs of tiles.
+    const int G = gridDim.x;
+    long long v = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    StreamTile<C> cur, nxt;
+    if (!sched.next(v, cur, wave, lane)) return;
+    v += G;
+    bool more = sched.next(v, nxt, wave, lane);
+
+    int tb = 0;
+    v4i wreg[D][KS][TI];
+    stream_tables<C>(cur, smem + C::kOffTables, wave, lane);
+#pragma unroll
+    for (int d = 0; d < D; ++d) {                 // every tile has at least D stages
+        const StreamSrc<C> src = stream_source<C>(cur, nxt, more, false, d);
+#pragma unroll
+        for (int ks = 0; ks < KS - 1; ++ks)
+#pragma unroll
+            for (int i = 0; i < TI; ++i) wreg[d][ks][i] = stream_load_w<C>(src, ks, i);
+        stream_load_x<C>(src, smem + d * C::kOpX, wave);
+#pragma unroll
+        for (int i = 0; i < TI; ++i) wreg[d][KS - 1][i] = stream_load_w<C>(src, KS - 1, i);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    v4i b[2][TJ];
+    wait_vm<C::kWaitFirst>();                     // tables and the ring loads of stage 0 have landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    stream_read_b(lds_base + offB, b[0], std::make_integer_sequence<int, TJ>{});
+
+    int s = 0;                                    // stage of the current tile being consumed
+    v16i acc[TI][TJ];
+    init_acc<C>(acc, tab_base, cur.p.off, lane, wave, 0);
+    bool done = false;
+    while (!done) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {             // ring slot and register set of the stage being consumed
+            unsigned cur_b = lds_base + d * C::kOpX + offB;
+            unsigned nxt_b = lds_base + ((d + 1) % D) * C::kOpX + offB;
+            asm volatile("" : "+v"(cur_b), "+v"(nxt_b));   // keeps the per-k-step addresses out of loop-invariant registers
+            const StreamSrc<C> src = stream_source<C>(cur, nxt, more, done, s + D);   // the stage requested now
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks < KS - 1) {
+                    // one wave per SIMD: the next k-step's operands are read under this k-step's MFMAs
+                    stream_read_b(cur_b ^ ((ks + 1) * 32), b[(ks + 1) & 1], std::make_integer_sequence<int, TJ>{});
+                    wait_lgkm<TJ>();
+                } else {
+                    // Once this stage's last operands are in registers every wave is done with its ring slot; the
+                    // ring loads of the next stage must have landed before anyone reads them.
+                    wait_vm<C::kWaitSteady>();
+                    wait_lgkm<0>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    stream_read_b(nxt_b, b[0], std::make_integer_sequence<int, TJ>{});
+                    if (s + D == cur.nk && more) stream_tables<C>(nxt, smem + C::kOffTables + (tb ^ 1) * T::kBytes, wave, lane);
+                    stream_load_x<C>(src, smem + d * C::kOpX, wave);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int j = 0; j < TJ; ++j) settle(b[ks & 1][j]);
+#pragma unroll
+                for (int i = 0; i < TI; ++i)
+#pragma unroll
+                    for (int j = 0; j < TJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[d][ks][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TI; ++i) wreg[d][ks][i] = stream_load_w<C>(src, ks, i);   // this k-step's registers are free again
+                __builtin_amdgcn_sched_barrier(0);
+            }
+
+            if (++s == cur.nk && !done) {         // the tile is complete (the same in every lane)
+                const LinearArgs& p = cur.p;
+                const unsigned tab = tab_base + tb * T::kBytes;
+                if (p.acc_dbg) {   // raw sums of code products for the bit-exact check (debug path, not tuned): the
+                                   // accumulators less the zero-point term they started from
+                    v16i start[TI][TJ];
+                    init_acc<C>(start, tab, p.off, lane, wave, 0);
+#pragma unroll
+                    for (int j = 0; j < TJ; ++j) {
+                        const long long m = cur.m0 + j * 32 + l32;
+#pragma unroll
+                        for (int i = 0; i < TI; ++i)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                const int o4 = cur.o0 + (wave * TI + i) * 32 + 8 * g + 4 * hi;
+                                if (m < p.M && o4 < p.N) {   // a global (not flat) store: a flat one would make every later wait vmcnt(0)
+                                    const v4i raw = {acc[i][j][4 * g] - start[i][j][4 * g], acc[i][j][4 * g + 1] - start[i][j][4 * g + 1],
+                                                     acc[i][j][4 * g + 2] - start[i][j][4 * g + 2], acc[i][j][4 * g + 3] - start[i][j][4 * g + 3]};
+                                    *(global_v4i*)(p.acc_dbg + m * p.N + o4) = raw;
+                                }
+                            }
+                    }
+                }
+                stream_epilogue<C>(p, cur.m0, cur.o0, acc, lds_base + C::kOffStaging + wave * C::kWaveStage, tab, lane, wave);
+                s = 0;
+                if (more) {
+                    // the next tile's tables were requested ahead of its first stage, whose ring loads every wave
+                    // waited for before the barrier of this tile's last stage
+                    init_acc<C>(acc, tab_base + (tb ^ 1) * T::kBytes, nxt.p.off, lane, wave, 0);
+                    cur = nxt;
+                    tb ^= 1;
+                    v += G;
+                    more = sched.next(v, nxt, wave, lane);
+                } else {
+                    done = true;
+                }
+            }
+        }
+    }
+    wait_lgkm<0>();                               // the last B prefetch read a slot nobody consumes; drain it
+}
+
+__global__ __launch_bounds__(StreamDecodeCfg::kThreads) void linear_stream_kernel(const LinearArgs single,
+                                                                                 const stwq_linear_problem* __restrict__ problems,
+                                                                                 int count, long long n_tiles, const GroupOrder order) {
+    typedef StreamDecodeCfg C;
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // ring, output staging, two tile tables, tile counts, order
+    constexpr int kOffPrefix = C::kOffTables + 2 * TileTables<C>::kBytes, kOffOrder = kOffPrefix + (kMaxGroup + 1) * 4;
+    int* prefix = reinterpret_cast<int*>(smem + kOffPrefix);
+    uint16_t* ord = reinterpret_cast<uint16_t*>(smem + kOffOrder);
+    if (problems) {   // plain LDS accesses: no direct-to-LDS load has been issued yet
+        for (int i = threadIdx.x; i < count; i += C::kThreads) {
+            const stwq_linear_problem& q = problems[order.v[i]];
+            ord[i] = order.v[i];
+            prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            prefix[0] = 0;
+            for (int i = 0; i < count; ++i) prefix[i + 1] += prefix[i];
+        }
+        __syncthreads();
+    }
+    StreamSched<C> sched;
+    sched.single = single;
+    sched.problems = problems;
+    sched.prefix = static_cast<unsigned>(reinterpret_cast<uintptr_t>(prefix));
+    sched.order = static_cast<unsigned>(reinterpret_cast<uintptr_t>(ord));
+    sched.n_tiles = n_tiles;
+    sched.cursor = 0;
+    stream_tiles<C>(sched, smem);
+}
+
+// Weights repacked for the streaming kernel: blocks of 32 channels x 32 K-bytes, 1 KB each, block (panel,
+// k-step) at (panel * K / 32 + k-step) KB; inside a block, lane l of the MFMA A operand (channel l % 32,
+// K bytes 16 (l / 32) .. + 15) sits at 16 l.  Channels past N are zero.
+__global__ __launch_bounds__(256) void pack_panel32_kernel(const int8_t* __restrict__ wq, int N, int K, int8_t* __restrict__ out) {
+    const long long chunk = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;     // one 16-byte chunk per thread
+    const long long total = static_cast<long long>((N + 31) / 32) * 32 * (K / 16);
+    if (chunk >= total) return;
+    const int lane = static_cast<int>(chunk % 64);
+    const long long blk = chunk / 64;
+    const int ksteps = K / 32;
+    const int kstep = static_cast<int>(blk % ksteps);
+    const int panel = static_cast<int>(blk / ksteps);
+    const int o = panel * 32 + lane % 32, k = kstep * 32 + (lane / 32) * 16;
+    int4 v = make_int4(0, 0, 0, 0);
+    if (o < N) v = *reinterpret_cast<const int4*>(wq + static_cast<size_t>(o) * K + k);
+    *reinterpret_cast<int4*>(out + chunk * 16) = v;
+}
+
+// True when the streaming kernel takes this K: whole 32-byte k-steps in pairs, and at least D stages.
+static bool stream_ok(int K) {
+    typedef StreamDecodeCfg C;
+    return K % 64 == 0 && (K + C::BK - 1) / C::BK >= C::D;
+}
+
 static int check_linear_args(const char* who, const int8_t* q, int64_t M, int K, int N, int L, const int8_t* wq,
                              const float* dw, const int32_t* wsum, const float* delta, const int32_t* zp, int a_bits,
                              const float* bias, const uint16_t* y, const int32_t* acc_dbg) {
@@ -841,6 +1330,22 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
     return launch_status("linear_prefill_kernel");
 }
 
+static int launch_stream(const stwq::LinearArgs& single, const stwq_linear_problem* problems_dev, int count, long long n_tiles,
+                         const stwq::GroupOrder& order, hipStream_t s) {
+    using namespace stwq;
+    typedef StreamDecodeCfg C;
+    constexpr int kLds = C::kOffTables + 2 * TileTables<C>::kBytes + (kMaxGroup + 1) * 4 + kMaxGroup * 2;
+    static_assert(kLds <= 160 * 1024, "LDS of one CU");
+    static const int attr = set_ring(linear_stream_kernel, kLds);
+    if (attr != STWQ_OK) return attr;
+    int cus = 0;
+    const int rc = compute_units(&cus);
+    if (rc != STWQ_OK) return rc;
+    const long long grid = n_tiles < cus ? n_tiles : cus;
+    linear_stream_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), kLds, s>>>(single, problems_dev, count, n_tiles, order);
+    return launch_status("linear_stream_kernel");
+}
+
 static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s) {
     using namespace stwq;
     const long long M = p.M;
@@ -872,6 +1377,16 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
         static const GroupOrder no_order = {};
         return launch_decode(p, nullptr, 0, n_tiles, no_order, s);
     }
+    if (schedule == STWQ_SCHEDULE_STREAM) {
+        typedef StreamDecodeCfg C;
+        if (!stream_ok(p.K))
+            return fail(STWQ_EUNSUPPORTED, "stwq_linear: the streaming schedule needs K %% 64 == 0 and K >= %d (K = %d)",
+                        C::BK * (C::D - 1) + 64, p.K);
+        const long long n_tiles = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
+        STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
+        static const GroupOrder no_order = {};
+        return launch_stream(p, nullptr, 0, n_tiles, no_order, s);
+    }
     if (schedule == STWQ_SCHEDULE_GENERIC) {
         const long long gx = (M + 63) / 64;
         const int gy = (p.N + 63) / 64;
@@ -885,25 +1400,56 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
 extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int count,
                                    const stwq_linear_problem* problems_dev, void* stream) {
     using namespace stwq;
-    typedef DecodeCfg C;
     clear_error();
     STWQ_REQUIRE(problems && problems_dev, "stwq_linear_grouped: null pointer");
     STWQ_REQUIRE(count > 0 && count <= kMaxGroup, "stwq_linear_grouped: count = %d must be in 1 .. %d", count, kMaxGroup);
-    long long n_tiles = 0;
+    // The streaming kernel takes the group when every problem has enough K stages for it; the tiled decode
+    // kernel otherwise (row-major weights only).
+    bool streaming = true, packed = false;
     for (int i = 0; i < count; ++i) {
         const stwq_linear_problem& q = problems[i];
         const int rc = check_linear_args("stwq_linear_grouped", q.q_dev, q.M, q.K, q.N, q.L, q.wq_dev, q.dw_dev, q.wsum_dev,
                                          q.delta_dev, q.zp_dev, q.a_bits, q.bias_dev, q.y_bf16_dev, q.acc_dbg_dev);
         if (rc != STWQ_OK) return rc;
+        STWQ_REQUIRE(q.w_layout == STWQ_LAYOUT_ROWMAJOR || q.w_layout == STWQ_LAYOUT_PANEL32,
+                     "stwq_linear_grouped: problem %d has w_layout = %d", i, q.w_layout);
         if (q.K % kBK != 0)
             return fail(STWQ_EUNSUPPORTED, "stwq_linear_grouped: problem %d has K = %d, needs K %% %d == 0", i, q.K, kBK);
-        n_tiles += static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+        streaming = streaming && stream_ok(q.K);
+        packed = packed || q.w_layout == STWQ_LAYOUT_PANEL32;
     }
+    if (packed && !streaming)
+        return fail(STWQ_EUNSUPPORTED, "stwq_linear_grouped: packed weights need K >= %d in every problem of the group",
+                    StreamDecodeCfg::BK * (StreamDecodeCfg::D - 1) + 64);
+    const int tile_m = streaming ? StreamDecodeCfg::kTileM : DecodeCfg::kTileM;
+    const int tile_o = streaming ? StreamDecodeCfg::kTileO : DecodeCfg::kTileO;
+    long long n_tiles = 0;
+    for (int i = 0; i < count; ++i)
+        n_tiles += static_cast<long long>((problems[i].M + tile_m - 1) / tile_m) * ((problems[i].N + tile_o - 1) / tile_o);
     STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear_grouped: too many tiles");
     GroupOrder order = {};
     for (int i = 0; i < count; ++i) order.v[i] = static_cast<uint16_t>(i);
     std::stable_sort(order.v, order.v + count, [&](uint16_t a, uint16_t b) { return problems[a].K > problems[b].K; });
-    return launch_decode(LinearArgs{}, problems_dev, count, n_tiles, order, static_cast<hipStream_t>(stream));
+    return streaming ? launch_stream(LinearArgs{}, problems_dev, count, n_tiles, order, static_cast<hipStream_t>(stream))
+                     : launch_decode(LinearArgs{}, problems_dev, count, n_tiles, order, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int stwq_pack_weights(const int8_t* wq_dev, int N, int K, int8_t* packed_dev, void* stream) {
+    using namespace stwq;
+    clear_error();
+    STWQ_REQUIRE(wq_dev && packed_dev, "stwq_pack_weights: null pointer");
+    STWQ_REQUIRE(N > 0 && K > 0 && K % 32 == 0, "stwq_pack_weights: N = %d, K = %d (K must be a positive multiple of 32)", N, K);
+    STWQ_REQUIRE(aligned16(wq_dev) && aligned16(packed_dev), "stwq_pack_weights: buffers must be 16-byte aligned");
+    const long long chunks = static_cast<long long>((N + 31) / 32) * 32 * (K / 16);
+    const long long blocks = (chunks + 255) / 256;
+    STWQ_REQUIRE(blocks <= 0x7FFFFFFFLL, "stwq_pack_weights: matrix too large");
+    pack_panel32_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(wq_dev, N, K, packed_dev);
+    return launch_status("pack_panel32_kernel");
+}
+
+extern "C" size_t stwq_packed_weight_bytes(int N, int K) {
+    if (N <= 0 || K <= 0) return 0;
+    return static_cast<size_t>((N + 31) / 32) * 32 * static_cast<size_t>(K);
 }
 
 extern "C" int stwq_linear_ex(const int8_t* q_dev, int64_t M, int K, int N, int L,

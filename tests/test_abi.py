@@ -55,7 +55,14 @@ def test_invalid_arguments_return_einval_without_a_gpu():
     assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 4, None) == -2      # so do the named tiles
     assert l.stwq_linear_ex(p, 300, 32, 16, 2, p, p, p, p, p, 8, None, p, None, 5, None) == -2
     assert b"64" in l.stwq_last_error()
-    assert l.stwq_linear_ex(p, 300, 64, 16, 2, p, p, p, p, p, 8, None, p, None, 6, None) == EINVAL  # unknown schedule
+    assert l.stwq_linear_ex(p, 100, 256, 16, 2, p, p, p, p, p, 8, None, p, None, 6, None) == -2     # streaming needs K >= 320
+    assert b"320" in l.stwq_last_error()
+    assert l.stwq_linear_ex(p, 300, 64, 16, 2, p, p, p, p, p, 8, None, p, None, 7, None) == EINVAL  # unknown schedule
+    assert l.stwq_pack_weights(None, 32, 64, p, None) == EINVAL
+    assert l.stwq_pack_weights(p, 32, 48, p, None) == EINVAL                                        # K % 32
+    assert l.stwq_pack_weights(p, 0, 64, p, None) == EINVAL
+    assert l.stwq_pack_weights(p, 32, 64, p + 8, None) == EINVAL                                    # alignment
+    assert l.stwq_packed_weight_bytes(33, 64) == 64 * 64 and l.stwq_packed_weight_bytes(0, 64) == 0
     assert l.stwq_linear_grouped(None, 1, p, None) == EINVAL
     assert l.stwq_linear_grouped(p, 0, p, None) == EINVAL
     assert l.stwq_quantize_act_grouped(None, 1, p, None) == EINVAL

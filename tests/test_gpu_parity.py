@@ -14,7 +14,7 @@ import gpu_common as G                       # noqa: E402
 
 F32 = np.float32
 SCHEDULES = {"generic": P.SCHEDULE_GENERIC, "prefill": P.SCHEDULE_PREFILL, "decode": P.SCHEDULE_DECODE,
-             "wide": P.SCHEDULE_PREFILL_WIDE, "narrow": P.SCHEDULE_PREFILL_NARROW}
+             "wide": P.SCHEDULE_PREFILL_WIDE, "narrow": P.SCHEDULE_PREFILL_NARROW, "stream": P.SCHEDULE_STREAM}
 
 
 def small_spec(**kw):
@@ -103,11 +103,14 @@ CASES = [
     ("odd_k_steps",    384,  264, 53, 11,    6,     6,    ("generic", "wide", "narrow")),
     ("one_tile",       128,  256, 64, 4,     6,     8,    ("wide", "narrow")),
     ("one_stage",      64,   136, 9,  15,    6,     8,    ("wide", "narrow")),
-    ("long_k",         1280, 136, 30, 5,     6,     8,    ("wide", "narrow", "prefill", "decode")),
-    # the streaming (decode) schedule: shortest K it takes, a ragged last K stage, ragged channel and row tiles
-    ("stream_min_k",   704,  264, 53, 3,     6,     8,    ("generic", "decode")),
-    ("stream_ragged",  832,  520, 131, 2,    6,     6,    ("generic", "wide", "narrow", "decode")),
-    ("stream_tiles",   768,  776, 300, 1,    4,     8,    ("wide", "narrow", "decode")),
+    ("long_k",         1280, 136, 30, 5,     6,     8,    ("wide", "narrow", "prefill", "stream", "decode")),
+    # the streaming schedule: shortest K it takes (three stages, the last half full), a ragged last K stage,
+    # ragged channel and row tiles, several tiles per workgroup
+    ("stream_k320",    320,  520, 70, 2,     6,     8,    ("generic", "stream")),
+    ("stream_k384",    384,  264, 53, 3,     6,     6,    ("decode", "stream")),
+    ("stream_min_k",   704,  264, 53, 3,     6,     8,    ("generic", "decode", "stream")),
+    ("stream_ragged",  832,  520, 131, 2,    6,     6,    ("generic", "wide", "narrow", "decode", "stream")),
+    ("stream_tiles",   768,  776, 300, 1,    4,     8,    ("wide", "narrow", "decode", "stream")),
 ]
 
 
@@ -136,7 +139,7 @@ def test_config1_full():
     layer = G.gpu_layer(spec, xc, w, b, pack["s"])
     G.check_calibration(layer, pack)
     results = {}
-    for sch in ("generic", "prefill", "wide", "narrow", "decode"):
+    for sch in ("generic", "prefill", "wide", "narrow", "decode", "stream"):
         results[sch] = G.check_forward(layer, pack, xt, SCHEDULES[sch], what=f"config1/{sch}")
     # run-to-run determinism and schedule independence of the integer part
     q2, acc2, y2 = G.check_forward(layer, pack, xt, SCHEDULES["prefill"], what="config1/prefill again")
@@ -144,6 +147,7 @@ def test_config1_full():
     assert torch.equal(results["generic"][1], results["prefill"][1]) and torch.equal(results["decode"][1], results["prefill"][1])
     assert torch.equal(results["wide"][2], results["narrow"][2]) and torch.equal(results["wide"][2], results["prefill"][2])
     assert torch.equal(results["decode"][2], results["prefill"][2])
+    assert torch.equal(results["stream"][1], results["prefill"][1]) and torch.equal(results["stream"][2], results["prefill"][2])
     # auto picks a schedule and agrees
     y_auto = layer.forward(G.dev(xt))
     assert torch.equal(y_auto, y2)
@@ -164,7 +168,7 @@ def test_edge_inputs(bits):
     x[3] = 1e-42
     x[4, ::2] = np.inf
     x[4, 1::2] = -np.inf
-    for sch in ("generic", "wide", "narrow", "decode"):
+    for sch in ("generic", "wide", "narrow", "decode", "stream"):
         q, acc, y = G.check_forward(layer, pack, x, SCHEDULES[sch], what=f"edges/{sch}")
         assert not y[0].float().abs().max().item() > 0
     codes = G.host(q).astype(np.int32) + O.store_offset(bits)
@@ -172,6 +176,7 @@ def test_edge_inputs(bits):
     # a single row
     G.check_forward(layer, pack, xt[:1], SCHEDULES["generic"], what="one row")
     G.check_forward(layer, pack, xt[:1], P.SCHEDULE_AUTO, what="one row/auto")
+    G.check_forward(layer, pack, xt[:1], P.SCHEDULE_STREAM, what="one row/stream")
 
 
 # ---------------------------------------------------------------- GPS scale
@@ -192,6 +197,27 @@ def test_gps_scale_matches_oracle(K, N, L, n, bits, mode):
     assert np.allclose(got, s_ref, rtol=1e-5, atol=0), np.abs(got / s_ref - 1).max()
     if K == 64:
         assert got[5] == 1 and got[9] == 1
+
+
+# ---------------------------------------------------------------- weight repacking (part of the fold step)
+
+@pytest.mark.parametrize("N,K", [(32, 32), (72, 160), (1288, 1344), (3840, 1280)])
+def test_pack_weights(N, K):
+    """Every byte of the panel layout against the address formula of the header; padded channels are zero."""
+    rng = np.random.default_rng(N * 7919 + K)
+    wq = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+    packed = torch.full((P.stwq_packed_weight_bytes(N, K),), 77, dtype=torch.int8, device=G.DEV)
+    P.stwq_pack_weights(torch.from_numpy(wq).to(G.DEV), packed)
+    torch.cuda.synchronize()
+    got = G.host(packed)
+    Np = (N + 31) // 32 * 32
+    assert got.size == Np * K
+    padded = np.zeros((Np, K), np.int8)
+    padded[:N] = wq
+    o, k = np.meshgrid(np.arange(Np), np.arange(K), indexing="ij")
+    addr = ((o // 32) * (K // 32) + k // 32) * 1024 + ((k % 32) // 16 * 32 + o % 32) * 16 + k % 16
+    assert np.array_equal(np.sort(addr.ravel()), np.arange(Np * K))          # a permutation of the buffer
+    assert np.array_equal(got[addr], padded)
 
 
 # ---------------------------------------------------------------- decode step: grouped launch
@@ -230,10 +256,59 @@ def test_decode_step_grouped():
     for spec, pr, (acc_ref, y_ref, pack) in zip(specs, problems, refs):
         assert np.array_equal(G.host(pr["acc_dbg"]), acc_ref), f"{spec.name} layer {spec.layer}: accumulators differ"
         G.check_bf16(pr["y"], y_ref, f"grouped {spec.name} {spec.layer}", pack["bias"])
-    # the single-launch decode schedule gives the same bits
+    # the same step on weights in the panel layout: identical accumulators and outputs
+    packed_problems = []
+    for spec, pr in zip(specs, problems):
+        packed = torch.empty(P.stwq_packed_weight_bytes(spec.N, spec.K), dtype=torch.int8, device=G.DEV)
+        P.stwq_pack_weights(pr["wq"], packed)
+        packed_problems.append(dict(pr, wq=packed, N=spec.N, w_layout=P.LAYOUT_PANEL32, y=torch.zeros_like(pr["y"]),
+                                    acc_dbg=torch.zeros_like(pr["acc_dbg"])))
+    packed_group = P.LinearGroup(packed_problems)
+    packed_group.run()
+    torch.cuda.synchronize()
+    for spec, pr, pp in zip(specs, problems, packed_problems):
+        assert torch.equal(pp["acc_dbg"], pr["acc_dbg"]), f"{spec.name} layer {spec.layer}: packed accumulators differ"
+        assert torch.equal(pp["y"], pr["y"]), f"{spec.name} layer {spec.layer}: packed outputs differ"
+    # the single-launch decode schedules give the same bits
     pr = problems[4]
+    y0 = torch.empty_like(pr["y"])
+    P.stwq_linear(pr["q"], pr["wq"], pr["dw"], pr["wsum"], pr["delta"], pr["zp"], 8, pr["bias"], y0, 1, None, P.SCHEDULE_STREAM)
+    assert torch.equal(y0, pr["y"])
     y1 = torch.empty_like(pr["y"])
     P.stwq_linear(pr["q"], pr["wq"], pr["dw"], pr["wsum"], pr["delta"], pr["zp"], 8, pr["bias"], y1, 1, None, P.SCHEDULE_DECODE)
     y2 = torch.empty_like(pr["y"])
     P.stwq_linear(pr["q"], pr["wq"], pr["dw"], pr["wsum"], pr["delta"], pr["zp"], 8, pr["bias"], y2, 1)      # auto
     assert torch.equal(y1, pr["y"]) and torch.equal(y2, pr["y"])
+
+
+def test_grouped_mixed_k():
+    """A group whose shortest K is below what the streaming kernel takes runs on the tiled decode kernel (row-major
+    weights only); mixed bit widths and ragged tiles in one launch."""
+    shapes = [(256, 264, 6), (384, 520, 8), (128, 136, 8)]
+    problems, refs = [], []
+    for K, N, bits in shapes:
+        spec = small_spec(K=K, N=N, L=9, batch=1, n_calib=6, a_bits=bits, w_bits=bits, n_outliers=8)
+        w, b, xc, xt = G.make_case(spec)
+        pack = G.oracle_pack(spec, xc, w, b)
+        layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+        q_ref, acc_ref, y_ref = O.forward(pack, xt)
+        q = layer.quantize(G.dev(xt))
+        assert np.array_equal(G.host(q), q_ref)
+        problems.append(dict(q=q, wq=layer.wq, dw=layer.dw, wsum=layer.wsum, delta=layer.delta, zp=layer.zp, a_bits=bits,
+                             bias=layer.bias, y=torch.zeros((spec.M, N), dtype=torch.bfloat16, device=G.DEV), L=spec.L,
+                             acc_dbg=torch.zeros((spec.M, N), dtype=torch.int32, device=G.DEV)))
+        refs.append((acc_ref, y_ref, pack, layer))
+    P.LinearGroup(problems).run()
+    torch.cuda.synchronize()
+    for pr, (acc_ref, y_ref, pack, _) in zip(problems, refs):
+        assert np.array_equal(G.host(pr["acc_dbg"]), acc_ref)
+        G.check_bf16(pr["y"], y_ref, "grouped mixed K", pack["bias"])
+    # packed weights cannot fall back
+    pr = problems[0]
+    packed = torch.empty(P.stwq_packed_weight_bytes(264, 256), dtype=torch.int8, device=G.DEV)
+    P.stwq_pack_weights(pr["wq"], packed)
+    with pytest.raises(P.StwqError) as e:
+        P.LinearGroup([dict(pr, wq=packed, N=264, w_layout=P.LAYOUT_PANEL32)]).run()
+    assert e.value.code == -2
+    with pytest.raises(P.StwqError):
+        P.LinearGroup([dict(pr, w_layout=5)]).run()
