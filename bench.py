@@ -91,9 +91,11 @@ def time_launches(fn, n_warm, n_iter):
     return ts[len(ts) // 2], sum(ts) / len(ts)
 
 
-def decode_step(device, n_iter=30):
+def decode_step(device, n_iter=30, rowmajor_too=False):
     """Configuration 4: one RAR-XXL-shaped decode step, 24 layers x (qkv, fc1, fc2), M = 128 rows at one token
-    position per layer, 432.5 MB of distinct int8 weights streamed once per step by ONE grouped launch."""
+    position per layer, 432.5 MB of distinct int8 weights streamed once per step by ONE grouped launch.  The
+    weights are in the panel layout (repacked once, with the fold); with rowmajor_too the row-major launch is timed
+    beside it (off by default: both run the same kernel, and a profile of the default run should hold one kind)."""
     import torch
     import workloads as wl
     import paper_2601_21238_amd as P
@@ -121,7 +123,16 @@ def decode_step(device, n_iter=30):
         del wd, xc
     torch.cuda.synchronize()
     log(f"decode step: 72 linears calibrated in {time.time() - t0:.1f} s")
-    group = P.LinearGroup(problems)
+    rmed = None
+    if rowmajor_too:
+        rowmajor_group = P.LinearGroup(problems)
+        rmed, _ = time_launches(rowmajor_group.run, 5, n_iter)
+    packed_problems = []
+    for spec, pr in zip(specs, problems):
+        packed = torch.empty(P.stwq_packed_weight_bytes(spec.N, spec.K), dtype=torch.int8, device=device)
+        P.stwq_pack_weights(pr["wq"], packed)
+        packed_problems.append(dict(pr, wq=packed, N=spec.N, w_layout=P.LAYOUT_PANEL32))
+    group = P.LinearGroup(packed_problems)
     med, mean = time_launches(group.run, 5, n_iter)
     w_bytes = float(sum(s.N * s.K for s in specs))
     all_bytes = float(sum(s.N * s.K + s.M * s.K + 2 * s.M * s.N + 12 * s.N + 8 for s in specs))
@@ -145,7 +156,8 @@ def decode_step(device, n_iter=30):
             "roofline": {"bound": "hbm", "achieved": all_bytes / mean / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": all_bytes / mean / 1e9 / HBM_PEAK_GBS,
                          "traffic": recorded_traffic("decode_linear_traffic_bytes_per_launch"),
-                         "kernel": "stwq::linear_decode_kernel", "avg_launch_us": mean * 1e6},
+                         "kernel": "stwq::linear_stream_kernel", "avg_launch_us": mean * 1e6},
+            "rowmajor_weights_us": None if rmed is None else rmed * 1e6,
             "quantize_72_launches_us": qmed * 1e6, "quantize_grouped_us": qgmed * 1e6,
             "step_us": smed * 1e6, "step_gbs": (all_bytes + q_bytes) / smed / 1e9,
             "step_frac_hbm_peak": (all_bytes + q_bytes) / smed / 1e9 / HBM_PEAK_GBS}
@@ -186,6 +198,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-rowmajor", action="store_true", help="also time the decode step on row-major weights")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1. "
@@ -279,7 +292,7 @@ def main() -> int:
     extra["fold"] = {"us": med * 1e6, "gbs": 5.0 * wd.numel() / med / 1e9,
                      "frac_hbm_peak": 5.0 * wd.numel() / med / 1e9 / HBM_PEAK_GBS}
     del xc, wd, tmp
-    extra["decode"] = decode_step(device)
+    extra["decode"] = decode_step(device, rowmajor_too=args.decode_rowmajor)
     # a plain device-to-device copy of known size: the reference that scales the FETCH_SIZE / WRITE_SIZE counters
     cal_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=device).normal_()
     cal_dst = torch.empty_like(cal_src)

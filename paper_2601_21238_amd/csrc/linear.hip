@@ -11,7 +11,10 @@
 // Inside one MFMA both operands take the same 16-byte K chunk per lane, and integer sums commute,
 // so any consistent assignment of K chunks to lanes gives the exact result.
 #include <algorithm>
+#include <functional>
+#include <queue>
 #include <utility>
+#include <vector>
 
 #include "common.h"
 
@@ -1027,19 +1030,38 @@ __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m
     }
 }
 
-// Decode schedule for the streaming kernel: tile v of the concatenated tile lists of the problems in
-// processing order (channel tiles fastest within a problem).
+// Decode schedule for the streaming kernel.  Tiles are numbered along the concatenated tile lists of the
+// problems in processing order (longest K first; channel tiles fastest within a problem).  A workgroup
+// either takes every gridDim.x-th tile, or, when the host has balanced the launch, the tiles of its own
+// list (increasing ids): tiles of a group differ several-fold in length (K) while a workgroup gets only a
+// handful, so dealing them out in turn leaves some workgroups with a third more work than the average.
+constexpr int kPlanEntries = 1792;
+struct GroupPlan {
+    // [0, count): problem index at each position of the processing order; when planned, then gridDim.x + 1
+    // list starts and after them the tile ids of all lists, one list per workgroup
+    uint16_t v[kPlanEntries];
+};
 template <class C>
 struct StreamSched {
     LinearArgs single;
     const stwq_linear_problem* problems;
     unsigned prefix;           // LDS address of count + 1 running tile counts, problems in processing order
     unsigned order;            // LDS address of the problem index (16 bits) at each position of that order
-    long long n_tiles;
+    unsigned list;             // LDS address of the tile ids (16 bits) of all lists, or 0: every gridDim.x-th tile
+    int pos, end;              // this workgroup's range in `list`
+    long long v, n_tiles;      // next tile id when there are no lists
     int cursor;                // position in the order of the previous tile (tiles are visited in increasing order)
-    __device__ __forceinline__ bool next(long long v, StreamTile<C>& t, int wave, int lane) {
-        if (v >= n_tiles) return false;
-        int tile = static_cast<int>(v);
+    __device__ __forceinline__ bool next(StreamTile<C>& t, int wave, int lane) {
+        int tile;
+        if (list) {
+            if (pos >= end) return false;
+            tile = __builtin_amdgcn_readfirstlane(lds_ld2_now(list + 2 * pos));
+            ++pos;
+        } else {
+            if (v >= n_tiles) return false;
+            tile = static_cast<int>(v);
+            v += gridDim.x;
+        }
         int layout = STWQ_LAYOUT_ROWMAJOR;
         if (problems) {
             int i = cursor;
@@ -1074,14 +1096,9 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
     // sits at this offset ^ 32 ks (the chunk index is (2 ks + hi) ^ swizzle and 2 ks has no low bit)
     const unsigned offB = l32 * C::BK + ((hi ^ ((l32 >> 1) & 7)) * 16);
 
-    // Tile ids of this workgroup: stride gridDim.x, starting at a permutation of the block id that
-    // gives the 8 XCDs contiguous runs of tiles.
-    const int G = gridDim.x;
-    long long v = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
     StreamTile<C> cur, nxt;
-    if (!sched.next(v, cur, wave, lane)) return;
-    v += G;
-    bool more = sched.next(v, nxt, wave, lane);
+    if (!sched.next(cur, wave, lane)) return;
+    bool more = sched.next(nxt, wave, lane);
 
     int tb = 0;
     v4i wreg[D][KS][TI];
@@ -1177,8 +1194,7 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
                     init_acc<C>(acc, tab_base + (tb ^ 1) * T::kBytes, nxt.p.off, lane, wave, 0);
                     cur = nxt;
                     tb ^= 1;
-                    v += G;
-                    more = sched.next(v, nxt, wave, lane);
+                    more = sched.next(nxt, wave, lane);
                 } else {
                     done = true;
                 }
@@ -1190,16 +1206,19 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
 
 __global__ __launch_bounds__(StreamDecodeCfg::kThreads) void linear_stream_kernel(const LinearArgs single,
                                                                                  const stwq_linear_problem* __restrict__ problems,
-                                                                                 int count, long long n_tiles, const GroupOrder order) {
+                                                                                 int count, long long n_tiles, int planned,
+                                                                                 const GroupPlan plan) {
     typedef StreamDecodeCfg C;
-    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // ring, output staging, two tile tables, tile counts, order
-    constexpr int kOffPrefix = C::kOffTables + 2 * TileTables<C>::kBytes, kOffOrder = kOffPrefix + (kMaxGroup + 1) * 4;
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // ring, output staging, two tile tables, tile counts, plan
+    constexpr int kOffPrefix = C::kOffTables + 2 * TileTables<C>::kBytes, kOffPlan = kOffPrefix + (kMaxGroup + 1) * 4;
     int* prefix = reinterpret_cast<int*>(smem + kOffPrefix);
-    uint16_t* ord = reinterpret_cast<uint16_t*>(smem + kOffOrder);
+    uint16_t* pl = reinterpret_cast<uint16_t*>(smem + kOffPlan);
+    const int G = gridDim.x;
     if (problems) {   // plain LDS accesses: no direct-to-LDS load has been issued yet
+        const int used = count + (planned ? G + 1 + static_cast<int>(n_tiles) : 0);
+        for (int i = threadIdx.x; i < used; i += C::kThreads) pl[i] = plan.v[i];
         for (int i = threadIdx.x; i < count; i += C::kThreads) {
-            const stwq_linear_problem& q = problems[order.v[i]];
-            ord[i] = order.v[i];
+            const stwq_linear_problem& q = problems[plan.v[i]];
             prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
         }
         __syncthreads();
@@ -1213,7 +1232,17 @@ __global__ __launch_bounds__(StreamDecodeCfg::kThreads) void linear_stream_kerne
     sched.single = single;
     sched.problems = problems;
     sched.prefix = static_cast<unsigned>(reinterpret_cast<uintptr_t>(prefix));
-    sched.order = static_cast<unsigned>(reinterpret_cast<uintptr_t>(ord));
+    sched.order = static_cast<unsigned>(reinterpret_cast<uintptr_t>(pl));
+    sched.list = 0;
+    sched.pos = sched.end = 0;
+    if (problems && planned) {
+        sched.list = sched.order + 2 * (count + G + 1);
+        sched.pos = pl[count + blockIdx.x];
+        sched.end = pl[count + blockIdx.x + 1];
+    }
+    // Without lists: stride gridDim.x from a permutation of the block id that gives the 8 XCDs (which take
+    // workgroup ids in turn) contiguous runs of tiles.
+    sched.v = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
     sched.n_tiles = n_tiles;
     sched.cursor = 0;
     stream_tiles<C>(sched, smem);
@@ -1330,11 +1359,63 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
     return launch_status("linear_prefill_kernel");
 }
 
-static int launch_stream(const stwq::LinearArgs& single, const stwq_linear_problem* problems_dev, int count, long long n_tiles,
-                         const stwq::GroupOrder& order, hipStream_t s) {
+// Tile lists for a grouped streaming launch: tiles in processing order (cost non-increasing) each go to the
+// workgroup with the least work so far.  The cost of a tile is its K stages plus the epilogue and tile
+// switch, about two and a half stages' worth.  Returns false when the lists do not fit the plan.
+static bool plan_stream_lists(const stwq_linear_problem* problems, int count, long long n_tiles, int grid, stwq::GroupPlan& plan) {
     using namespace stwq;
     typedef StreamDecodeCfg C;
-    constexpr int kLds = C::kOffTables + 2 * TileTables<C>::kBytes + (kMaxGroup + 1) * 4 + kMaxGroup * 2;
+    if (grid > 0xFFFF || count + grid + 1 + n_tiles > kPlanEntries) return false;
+    // the last plan, kept per thread: a decode loop launches the same group of shapes every step
+    struct Key { int M, K, N; };
+    thread_local std::vector<Key> last_key;
+    thread_local int last_grid = 0;
+    thread_local GroupPlan last_plan;
+    bool same = last_grid == grid && static_cast<int>(last_key.size()) == count;
+    for (int i = 0; same && i < count; ++i)
+        same = last_key[i].M == problems[i].M && last_key[i].K == problems[i].K && last_key[i].N == problems[i].N;
+    if (same) {
+        plan = last_plan;
+        return true;
+    }
+    std::vector<std::vector<uint16_t>> lists(grid);
+    typedef std::pair<long long, int> Load;                       // (work so far, workgroup)
+    std::priority_queue<Load, std::vector<Load>, std::greater<Load>> least;
+    for (int g = 0; g < grid; ++g) least.push(Load(0, g));
+    int tile = 0;
+    for (int i = 0; i < count; ++i) {
+        const stwq_linear_problem& q = problems[plan.v[i]];
+        const int tiles = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+        const long long cost = 2LL * ((q.K + C::BK - 1) / C::BK) + 5;
+        for (int t = 0; t < tiles; ++t, ++tile) {
+            Load l = least.top();
+            least.pop();
+            lists[l.second].push_back(static_cast<uint16_t>(tile));
+            l.first += cost;
+            least.push(l);
+        }
+    }
+    uint16_t* start = plan.v + count;
+    uint16_t* out = start + grid + 1;
+    int n = 0;
+    for (int g = 0; g < grid; ++g) {
+        start[g] = static_cast<uint16_t>(n);
+        for (uint16_t t : lists[g]) out[n++] = t;
+    }
+    start[grid] = static_cast<uint16_t>(n);
+    last_key.resize(count);
+    for (int i = 0; i < count; ++i) last_key[i] = Key{problems[i].M, problems[i].K, problems[i].N};
+    last_grid = grid;
+    last_plan = plan;
+    return true;
+}
+
+// problems: host descriptors of a grouped launch (nullptr for a single problem); plan.v[0 .. count) holds the processing order.
+static int launch_stream(const stwq::LinearArgs& single, const stwq_linear_problem* problems, const stwq_linear_problem* problems_dev,
+                         int count, long long n_tiles, stwq::GroupPlan& plan, hipStream_t s) {
+    using namespace stwq;
+    typedef StreamDecodeCfg C;
+    constexpr int kLds = C::kOffTables + 2 * TileTables<C>::kBytes + (kMaxGroup + 1) * 4 + kPlanEntries * 2;
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     static const int attr = set_ring(linear_stream_kernel, kLds);
     if (attr != STWQ_OK) return attr;
@@ -1342,7 +1423,9 @@ static int launch_stream(const stwq::LinearArgs& single, const stwq_linear_probl
     const int rc = compute_units(&cus);
     if (rc != STWQ_OK) return rc;
     const long long grid = n_tiles < cus ? n_tiles : cus;
-    linear_stream_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), kLds, s>>>(single, problems_dev, count, n_tiles, order);
+    const bool planned = problems && n_tiles > grid && plan_stream_lists(problems, count, n_tiles, static_cast<int>(grid), plan);
+    linear_stream_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), kLds, s>>>(single, problems_dev, count, n_tiles,
+                                                                                           planned ? 1 : 0, plan);
     return launch_status("linear_stream_kernel");
 }
 
@@ -1384,8 +1467,8 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
                         C::BK * (C::D - 1) + 64, p.K);
         const long long n_tiles = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
         STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
-        static const GroupOrder no_order = {};
-        return launch_stream(p, nullptr, 0, n_tiles, no_order, s);
+        static GroupPlan no_plan = {};
+        return launch_stream(p, nullptr, nullptr, 0, n_tiles, no_plan, s);
     }
     if (schedule == STWQ_SCHEDULE_GENERIC) {
         const long long gx = (M + 63) / 64;
@@ -1421,17 +1504,27 @@ extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int coun
     if (packed && !streaming)
         return fail(STWQ_EUNSUPPORTED, "stwq_linear_grouped: packed weights need K >= %d in every problem of the group",
                     StreamDecodeCfg::BK * (StreamDecodeCfg::D - 1) + 64);
+    // Row-major weights stay on the tiled kernel: a wave-wide load of the streaming kernel would touch 32 rows of 32
+    // bytes each, which costs more than the tiled kernel's detour through LDS.
+    streaming = streaming && packed;
     const int tile_m = streaming ? StreamDecodeCfg::kTileM : DecodeCfg::kTileM;
     const int tile_o = streaming ? StreamDecodeCfg::kTileO : DecodeCfg::kTileO;
     long long n_tiles = 0;
     for (int i = 0; i < count; ++i)
         n_tiles += static_cast<long long>((problems[i].M + tile_m - 1) / tile_m) * ((problems[i].N + tile_o - 1) / tile_o);
     STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear_grouped: too many tiles");
-    GroupOrder order = {};
-    for (int i = 0; i < count; ++i) order.v[i] = static_cast<uint16_t>(i);
-    std::stable_sort(order.v, order.v + count, [&](uint16_t a, uint16_t b) { return problems[a].K > problems[b].K; });
-    return streaming ? launch_stream(LinearArgs{}, problems_dev, count, n_tiles, order, static_cast<hipStream_t>(stream))
-                     : launch_decode(LinearArgs{}, problems_dev, count, n_tiles, order, static_cast<hipStream_t>(stream));
+    // processing order: longest K first, so that the long tiles are dealt out first
+    std::vector<uint16_t> order(count);
+    for (int i = 0; i < count; ++i) order[i] = static_cast<uint16_t>(i);
+    std::stable_sort(order.begin(), order.end(), [&](uint16_t a, uint16_t b) { return problems[a].K > problems[b].K; });
+    if (streaming) {
+        GroupPlan plan;
+        std::copy(order.begin(), order.end(), plan.v);
+        return launch_stream(LinearArgs{}, problems, problems_dev, count, n_tiles, plan, static_cast<hipStream_t>(stream));
+    }
+    GroupOrder go = {};
+    std::copy(order.begin(), order.end(), go.v);
+    return launch_decode(LinearArgs{}, problems_dev, count, n_tiles, go, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int stwq_pack_weights(const int8_t* wq_dev, int N, int K, int8_t* packed_dev, void* stream) {

@@ -261,8 +261,11 @@ def test_decode_step_grouped():
     for spec, pr in zip(specs, problems):
         packed = torch.empty(P.stwq_packed_weight_bytes(spec.N, spec.K), dtype=torch.int8, device=G.DEV)
         P.stwq_pack_weights(pr["wq"], packed)
-        packed_problems.append(dict(pr, wq=packed, N=spec.N, w_layout=P.LAYOUT_PANEL32, y=torch.zeros_like(pr["y"]),
-                                    acc_dbg=torch.zeros_like(pr["acc_dbg"])))
+        fresh = dict(y=torch.zeros_like(pr["y"]), acc_dbg=torch.zeros_like(pr["acc_dbg"]))
+        if len(packed_problems) == 1:       # one problem stays row-major: a group may mix the layouts
+            packed_problems.append(dict(pr, **fresh))
+        else:
+            packed_problems.append(dict(pr, wq=packed, N=spec.N, w_layout=P.LAYOUT_PANEL32, **fresh))
     packed_group = P.LinearGroup(packed_problems)
     packed_group.run()
     torch.cuda.synchronize()
@@ -312,3 +315,44 @@ def test_grouped_mixed_k():
     assert e.value.code == -2
     with pytest.raises(P.StwqError):
         P.LinearGroup([dict(pr, w_layout=5)]).run()
+
+
+def test_grouped_balanced_lists():
+    """A packed group with more tiles than compute units and a four-fold spread of K: the launch runs from
+    per-workgroup tile lists.  Sixty problems over three layers (they share weights, not inputs or outputs);
+    every accumulator and output is compared, and a second launch of the same group gives the same bits."""
+    layers = []
+    for K, bits in ((320, 8), (640, 6), (1280, 8)):
+        spec = small_spec(K=K, N=2312, L=5, batch=100, n_calib=4, a_bits=bits, w_bits=bits, n_outliers=8)
+        w, b, xc, xt = G.make_case(spec)
+        pack = G.oracle_pack(spec, xc, w, b)
+        layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+        packed = torch.empty(P.stwq_packed_weight_bytes(spec.N, K), dtype=torch.int8, device=G.DEV)
+        P.stwq_pack_weights(layer.wq, packed)
+        layers.append((spec, pack, layer, packed, xt))
+    problems, refs = [], []
+    for i in range(60):
+        spec, pack, layer, packed, xt = layers[i % 3]
+        t0 = i % spec.L
+        x = np.ascontiguousarray(xt[t0::spec.L][:100 if i % 7 else 23])      # rows at one position, ragged row tile
+        q_ref, acc_ref, y_ref = O.forward(pack, x, t0=t0)
+        q = layer.quantize(G.dev(x), t0=t0)
+        M = x.shape[0]
+        problems.append(dict(q=q, wq=packed, N=spec.N, w_layout=P.LAYOUT_PANEL32, dw=layer.dw, wsum=layer.wsum,
+                             delta=layer.delta[t0:t0 + 1], zp=layer.zp[t0:t0 + 1], a_bits=spec.a_bits, bias=layer.bias, L=1,
+                             y=torch.zeros((M, spec.N), dtype=torch.bfloat16, device=G.DEV),
+                             acc_dbg=torch.zeros((M, spec.N), dtype=torch.int32, device=G.DEV)))
+        refs.append((acc_ref, y_ref, pack))
+    group = P.LinearGroup(problems)
+    group.run()
+    torch.cuda.synchronize()
+    first = []
+    for i, (pr, (acc_ref, y_ref, pack)) in enumerate(zip(problems, refs)):
+        assert np.array_equal(G.host(pr["acc_dbg"]), acc_ref), f"problem {i}: accumulators differ"
+        G.check_bf16(pr["y"], y_ref, f"balanced group, problem {i}", pack["bias"])
+        first.append(pr["y"].clone())
+        pr["y"].zero_()
+    group.run()                                     # the cached lists
+    torch.cuda.synchronize()
+    for pr, y in zip(problems, first):
+        assert torch.equal(pr["y"], y)
