@@ -688,6 +688,32 @@ constexpr int kMaxGroup = 1024;
 struct GroupOrder {
     uint16_t v[kMaxGroup];
 };
+// prefix[1 .. count] (LDS) holds tile counts on entry and their running sums on exit, prefix[0] = 0.  Done by the
+// first wave, each lane summing a run of consecutive entries, with one scan across the lanes in between:
+// a single thread walking a thousand entries through LDS would hold the whole launch up for microseconds.
+__device__ __forceinline__ void running_tile_counts(int* prefix, int count) {
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x, per = (count + 63) / 64;
+    int sum = 0;
+    for (int k = 0; k < per; ++k) {
+        const int i = lane * per + k;
+        if (i < count) sum += prefix[i + 1];
+    }
+    int incl = sum;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    int run = incl - sum;
+    for (int k = 0; k < per; ++k) {
+        const int i = lane * per + k;
+        if (i < count) {
+            run += prefix[i + 1];
+            prefix[i + 1] = run;
+        }
+    }
+    if (lane == 0) prefix[0] = 0;
+}
 struct DecodeSched {
     LinearArgs single;
     const stwq_linear_problem* problems;
@@ -741,10 +767,7 @@ __global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(cons
             prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            prefix[0] = 0;
-            for (int i = 0; i < count; ++i) prefix[i + 1] += prefix[i];
-        }
+        running_tile_counts(prefix, count);
         __syncthreads();
     }
     DecodeSched sched;
@@ -942,7 +965,9 @@ template <class C>
 __device__ __forceinline__ v4i stream_load_w(const StreamSrc<C>& r, int ks, int i) {
     const int8_t* a = r.w[i] + static_cast<long long>(r.kstep + ks) * r.kstep_stride;
     if (ks >= r.valid_ks) a = reinterpret_cast<const int8_t*>(kZeros);
-    return *(const global_v4i*)a;                 // a global (not flat) load, tracked by the compiler
+    // A global (not flat) load, tracked by the compiler.  Non-temporal: every weight byte is read once, and kept out
+    // of the way it leaves the L2 to the activation rows, which all workgroups of a problem read.
+    return __builtin_nontemporal_load((const global_v4i*)a);
 }
 // The ring loads of the requested stage into the slot at `slot`.
 template <class C>
@@ -1222,10 +1247,7 @@ __global__ __launch_bounds__(StreamDecodeCfg::kThreads) void linear_stream_kerne
             prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            prefix[0] = 0;
-            for (int i = 0; i < count; ++i) prefix[i + 1] += prefix[i];
-        }
+        running_tile_counts(prefix, count);
         __syncthreads();
     }
     StreamSched<C> sched;
@@ -1361,7 +1383,8 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
 
 // Tile lists for a grouped streaming launch: tiles in processing order (cost non-increasing) each go to the
 // workgroup with the least work so far.  The cost of a tile is its K stages plus the epilogue and tile
-// switch, about two and a half stages' worth.  Returns false when the lists do not fit the plan.
+// switch, measured at 3.4 stages' worth (the output tile is a quarter of the bytes of an 11-stage tile's
+// weights).  Returns false when the lists do not fit the plan.
 static bool plan_stream_lists(const stwq_linear_problem* problems, int count, long long n_tiles, int grid, stwq::GroupPlan& plan) {
     using namespace stwq;
     typedef StreamDecodeCfg C;
@@ -1386,7 +1409,7 @@ static bool plan_stream_lists(const stwq_linear_problem* problems, int count, lo
     for (int i = 0; i < count; ++i) {
         const stwq_linear_problem& q = problems[plan.v[i]];
         const int tiles = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
-        const long long cost = 2LL * ((q.K + C::BK - 1) / C::BK) + 5;
+        const long long cost = 5LL * ((q.K + C::BK - 1) / C::BK) + 17;
         for (int t = 0; t < tiles; ++t, ++tile) {
             Load l = least.top();
             least.pop();

@@ -319,11 +319,11 @@ def test_grouped_mixed_k():
 
 def test_grouped_balanced_lists():
     """A packed group with more tiles than compute units and a four-fold spread of K: the launch runs from
-    per-workgroup tile lists.  Sixty problems over three layers (they share weights, not inputs or outputs);
+    per-workgroup tile lists.  130 problems over three layers (they share weights, not inputs or outputs);
     every accumulator and output is compared, and a second launch of the same group gives the same bits."""
     layers = []
     for K, bits in ((320, 8), (640, 6), (1280, 8)):
-        spec = small_spec(K=K, N=2312, L=5, batch=100, n_calib=4, a_bits=bits, w_bits=bits, n_outliers=8)
+        spec = small_spec(K=K, N=1032, L=5, batch=100, n_calib=4, a_bits=bits, w_bits=bits, n_outliers=8)
         w, b, xc, xt = G.make_case(spec)
         pack = G.oracle_pack(spec, xc, w, b)
         layer = G.gpu_layer(spec, xc, w, b, pack["s"])
@@ -331,7 +331,7 @@ def test_grouped_balanced_lists():
         P.stwq_pack_weights(layer.wq, packed)
         layers.append((spec, pack, layer, packed, xt))
     problems, refs = [], []
-    for i in range(60):
+    for i in range(130):
         spec, pack, layer, packed, xt = layers[i % 3]
         t0 = i % spec.L
         x = np.ascontiguousarray(xt[t0::spec.L][:100 if i % 7 else 23])      # rows at one position, ragged row tile
