@@ -72,4 +72,31 @@ __device__ __forceinline__ int quant_code(float pre, float inv_delta, float zf, 
     return static_cast<int>(fminf(fmaxf(r + zf, 0.0f), qmax));
 }
 
+// prefix[1 .. count] (LDS) holds counts on entry and their running sums on exit, prefix[0] = 0.  Done by the
+// first wave, each lane summing a run of consecutive entries, with one scan across the lanes in between:
+// a single thread walking a thousand entries through LDS would hold the whole launch up for microseconds.
+__device__ __forceinline__ void running_counts(int* prefix, int count) {
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x, per = (count + 63) / 64;
+    int sum = 0;
+    for (int k = 0; k < per; ++k) {
+        const int i = lane * per + k;
+        if (i < count) sum += prefix[i + 1];
+    }
+    int incl = sum;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    int run = incl - sum;
+    for (int k = 0; k < per; ++k) {
+        const int i = lane * per + k;
+        if (i < count) {
+            run += prefix[i + 1];
+            prefix[i + 1] = run;
+        }
+    }
+    if (lane == 0) prefix[0] = 0;
+}
+
 }  // namespace stwq

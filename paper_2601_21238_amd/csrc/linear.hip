@@ -688,32 +688,6 @@ constexpr int kMaxGroup = 1024;
 struct GroupOrder {
     uint16_t v[kMaxGroup];
 };
-// prefix[1 .. count] (LDS) holds tile counts on entry and their running sums on exit, prefix[0] = 0.  Done by the
-// first wave, each lane summing a run of consecutive entries, with one scan across the lanes in between:
-// a single thread walking a thousand entries through LDS would hold the whole launch up for microseconds.
-__device__ __forceinline__ void running_tile_counts(int* prefix, int count) {
-    if (threadIdx.x >= 64) return;
-    const int lane = threadIdx.x, per = (count + 63) / 64;
-    int sum = 0;
-    for (int k = 0; k < per; ++k) {
-        const int i = lane * per + k;
-        if (i < count) sum += prefix[i + 1];
-    }
-    int incl = sum;
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-    }
-    int run = incl - sum;
-    for (int k = 0; k < per; ++k) {
-        const int i = lane * per + k;
-        if (i < count) {
-            run += prefix[i + 1];
-            prefix[i + 1] = run;
-        }
-    }
-    if (lane == 0) prefix[0] = 0;
-}
 struct DecodeSched {
     LinearArgs single;
     const stwq_linear_problem* problems;
@@ -767,7 +741,7 @@ __global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(cons
             prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
         }
         __syncthreads();
-        running_tile_counts(prefix, count);
+        running_counts(prefix, count);
         __syncthreads();
     }
     DecodeSched sched;
@@ -814,30 +788,32 @@ __global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(cons
 //     wave-wide load reads 1 KB of consecutive bytes.  Both are "lane base + k-step x stride".
 // Tile tables, accumulator start, epilogue arithmetic and tile order are those of the tiled kernels.
 // ------------------------------------------------------------------------------------------------
-template <int D_>
+template <int D_, int BK_, int WGS_>
 struct StreamCfg {
     static constexpr int D = D_;                          // stages in flight = ring slots = weight register sets
-    static constexpr int BK = 128, kKS = BK / 32;         // bytes of K per stage; MFMA k-steps per stage
+    static constexpr int BK = BK_, kKS = BK / 32;         // bytes of K per stage (64 or 128); MFMA k-steps per stage
+    static constexpr int kWgsPerCu = WGS_;                // 1: all 512 registers for the one wave of a SIMD; 2: 256 each
     static constexpr int kWaves = 4, kThreads = 256;
     static constexpr int TI = 2, TJ = 4;                  // MFMA tiles per wave: 64 channels x 128 rows
     static constexpr int kTileO = kWaves * TI * 32, kTileM = TJ * 32;
     static constexpr int kChunks = TI * 4;                // 16-byte bf16 chunks per staged output row
     static constexpr int kOpX = kTileM * BK;              // one ring slot
     static constexpr int kRing = D * kOpX;
-    static constexpr int kLoadsX = kOpX / 1024 / kWaves;  // direct-to-LDS loads per wave and stage (8 rows each)
+    static constexpr int kRowsPerLoad = 1024 / BK;        // rows of one direct-to-LDS load (1 KB)
+    static constexpr int kLoadsX = kOpX / 1024 / kWaves;  // direct-to-LDS loads per wave and stage
     static constexpr int kLoadsW = kKS * TI;              // weight loads per wave and stage
     static constexpr int kOps = kLoadsX + kLoadsW;
     static constexpr int kWaveStage = 32 * TI * 64;       // output staging: 32 rows x 64 channels of bf16
     static constexpr int kJPerPass = 1;
     static constexpr int kOffStaging = kRing, kOffTables = kRing + kWaves * kWaveStage;
     // Ring wait in the steady state: operations issued after the awaited stage's ring loads.  A stage is
-    // requested as W(k-steps 0 .. 2) | X x kLoadsX | W(k-step 3); awaited are the X loads of the stage after the
+    // requested as W(all k-steps but the last) | X x kLoadsX | W(last k-step); awaited are the X loads of the stage after the
     // current one.  One less than the count, in case the compiler swaps a weight load with a ring load.
     static constexpr int kWaitSteady = TI + kOps * (D - 2) + TI * (kKS - 1) - 1;
     static constexpr int kWaitFirst = TI + kOps * (D - 1) - 1;
     static_assert(D >= 2 && kWaitFirst <= 63, "vmcnt is a 6-bit counter");
 };
-typedef StreamCfg<3> StreamDecodeCfg;
+typedef StreamCfg<3, 128, 1> StreamDecodeCfg;
 
 typedef __attribute__((address_space(1))) v4i global_v4i;
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void* base, unsigned bytes) {
@@ -869,14 +845,20 @@ struct StreamTile {
     unsigned xoff;       // this lane's byte offset from xbase at K position 0 in the first ring load
 };
 
-// Row and logical 16-byte chunk behind lane `lane` of this wave's u-th ring load (8 rows of 128 bytes;
-// the chunks of row r are permuted by chunk ^ ((r >> 1) & 7), applied on the global side).
+// Row and logical 16-byte chunk behind lane `lane` of this wave's u-th ring load (1 KB: 8 rows of 128
+// bytes or 16 of 64).  The chunks of row r are permuted, on the global side, by chunk ^ ring_swizzle(r),
+// which makes the operand reads (32 consecutive rows, one chunk each) free of bank conflicts.
+template <class C>
+__device__ __forceinline__ int ring_swizzle(int row) {
+    return C::BK == 128 ? (row >> 1) & 7 : (row >> 2) & 3;
+}
 template <class C>
 __device__ __forceinline__ int ring_row(int u, int wave, int lane) {
-    return (u * C::kWaves + wave) * 8 + lane / 8;
+    return (u * C::kWaves + wave) * C::kRowsPerLoad + lane / (C::BK / 16);
 }
+template <class C>
 __device__ __forceinline__ int ring_chunk(int row, int lane) {
-    return (lane % 8) ^ ((row >> 1) & 7);
+    return (lane % (C::BK / 16)) ^ ring_swizzle<C>(row);
 }
 
 template <class C>
@@ -898,9 +880,9 @@ __device__ __forceinline__ void stream_prepare(StreamTile<C>& t, int w_layout, i
     t.xbase = p.q + static_cast<size_t>(t.m0) * p.K;
     const unsigned long long rest = static_cast<unsigned long long>(p.M - t.m0) * p.K;
     t.xbytes = rest < 0xFFFFFFFFull ? static_cast<unsigned>(rest) : 0xFFFFFFFFu;
-    {   // ring load u covers rows 32 u + 8 wave + lane / 8: the same chunk permutation for every u
+    {   // the rows of ring load u are those of load 0 plus a multiple of 32: the same chunk permutation for every u
         const int r = ring_row<C>(0, wave, lane);
-        t.xoff = static_cast<unsigned>(r) * p.K + ring_chunk(r, lane) * 16;
+        t.xoff = static_cast<unsigned>(r) * p.K + ring_chunk<C>(r, lane) * 16;
     }
     t.nk = (p.K + C::BK - 1) / C::BK;
     t.tail_ks = (p.K % C::BK) / 32;
@@ -977,12 +959,12 @@ __device__ __forceinline__ void stream_load_x(const StreamSrc<C>& r, int8_t* slo
 #pragma unroll
     for (int u = 0; u < C::kLoadsX; ++u)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(slot + (u * C::kWaves + wave) * 1024), 16,
-                                                 r.xoff + static_cast<unsigned>(u * C::kWaves * 8 * r.K + r.kstep * 32), 0, 0, 0);
+                                                 r.xoff + static_cast<unsigned>(u * C::kWaves * C::kRowsPerLoad * r.K + r.kstep * 32), 0, 0, 0);
 }
 
-template <int... J>
+template <class C, int... J>
 __device__ __forceinline__ void stream_read_b(unsigned addr, v4i (&b)[sizeof...(J)], std::integer_sequence<int, J...>) {
-    ((b[J] = lds_read16<J * 32 * 128>(addr)), ...);
+    ((b[J] = lds_read16<J * 32 * C::BK>(addr)), ...);
 }
 
 // Epilogue of the streaming kernel (the arithmetic of `epilogue`).  One wave per SIMD: nobody else
@@ -1119,7 +1101,7 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
 
     // LDS byte offset (from the start of a ring slot) of this lane's B operand for k-step 0; k-step ks
     // sits at this offset ^ 32 ks (the chunk index is (2 ks + hi) ^ swizzle and 2 ks has no low bit)
-    const unsigned offB = l32 * C::BK + ((hi ^ ((l32 >> 1) & 7)) * 16);
+    const unsigned offB = l32 * C::BK + ((hi ^ ring_swizzle<C>(l32)) * 16);
 
     StreamTile<C> cur, nxt;
     if (!sched.next(cur, wave, lane)) return;
@@ -1144,7 +1126,7 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
     wait_vm<C::kWaitFirst>();                     // tables and the ring loads of stage 0 have landed
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    stream_read_b(lds_base + offB, b[0], std::make_integer_sequence<int, TJ>{});
+    stream_read_b<C>(lds_base + offB, b[0], std::make_integer_sequence<int, TJ>{});
 
     int s = 0;                                    // stage of the current tile being consumed
     v16i acc[TI][TJ];
@@ -1161,7 +1143,7 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks < KS - 1) {
                     // one wave per SIMD: the next k-step's operands are read under this k-step's MFMAs
-                    stream_read_b(cur_b ^ ((ks + 1) * 32), b[(ks + 1) & 1], std::make_integer_sequence<int, TJ>{});
+                    stream_read_b<C>(cur_b ^ ((ks + 1) * 32), b[(ks + 1) & 1], std::make_integer_sequence<int, TJ>{});
                     wait_lgkm<TJ>();
                 } else {
                     // Once this stage's last operands are in registers every wave is done with its ring slot; the
@@ -1170,7 +1152,7 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
                     wait_lgkm<0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
-                    stream_read_b(nxt_b, b[0], std::make_integer_sequence<int, TJ>{});
+                    stream_read_b<C>(nxt_b, b[0], std::make_integer_sequence<int, TJ>{});
                     if (s + D == cur.nk && more) stream_tables<C>(nxt, smem + C::kOffTables + (tb ^ 1) * T::kBytes, wave, lane);
                     stream_load_x<C>(src, smem + d * C::kOpX, wave);
                     __builtin_amdgcn_sched_barrier(0);
@@ -1211,7 +1193,10 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
                             }
                     }
                 }
-                stream_epilogue<C>(p, cur.m0, cur.o0, acc, lds_base + C::kOffStaging + wave * C::kWaveStage, tab, lane, wave);
+                if (C::kWgsPerCu == 1)
+                    stream_epilogue<C>(p, cur.m0, cur.o0, acc, lds_base + C::kOffStaging + wave * C::kWaveStage, tab, lane, wave);
+                else   // half the registers and a second wave on the SIMD to cover LDS round trips: constants are fetched per chunk
+                    epilogue<C, false>(p, cur.m0, cur.o0, acc, lds_base + C::kOffStaging + wave * C::kWaveStage, tab, lane, wave, 0);
                 s = 0;
                 if (more) {
                     // the next tile's tables were requested ahead of its first stage, whose ring loads every wave
@@ -1229,11 +1214,11 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
     wait_lgkm<0>();                               // the last B prefetch read a slot nobody consumes; drain it
 }
 
-__global__ __launch_bounds__(StreamDecodeCfg::kThreads) void linear_stream_kernel(const LinearArgs single,
-                                                                                 const stwq_linear_problem* __restrict__ problems,
-                                                                                 int count, long long n_tiles, int planned,
-                                                                                 const GroupPlan plan) {
-    typedef StreamDecodeCfg C;
+template <class C>
+__global__ __launch_bounds__(C::kThreads, C::kWgsPerCu) void linear_stream_kernel(const LinearArgs single,
+                                                                                const stwq_linear_problem* __restrict__ problems,
+                                                                                int count, long long n_tiles, int planned,
+                                                                                const GroupPlan plan) {
     extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // ring, output staging, two tile tables, tile counts, plan
     constexpr int kOffPrefix = C::kOffTables + 2 * TileTables<C>::kBytes, kOffPlan = kOffPrefix + (kMaxGroup + 1) * 4;
     int* prefix = reinterpret_cast<int*>(smem + kOffPrefix);
@@ -1247,7 +1232,7 @@ __global__ __launch_bounds__(StreamDecodeCfg::kThreads) void linear_stream_kerne
             prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
         }
         __syncthreads();
-        running_tile_counts(prefix, count);
+        running_counts(prefix, count);
         __syncthreads();
     }
     StreamSched<C> sched;
@@ -1385,9 +1370,9 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
 // workgroup with the least work so far.  The cost of a tile is its K stages plus the epilogue and tile
 // switch, measured at 3.4 stages' worth (the output tile is a quarter of the bytes of an 11-stage tile's
 // weights).  Returns false when the lists do not fit the plan.
+template <class C>
 static bool plan_stream_lists(const stwq_linear_problem* problems, int count, long long n_tiles, int grid, stwq::GroupPlan& plan) {
     using namespace stwq;
-    typedef StreamDecodeCfg C;
     if (grid > 0xFFFF || count + grid + 1 + n_tiles > kPlanEntries) return false;
     // the last plan, kept per thread: a decode loop launches the same group of shapes every step
     struct Key { int M, K, N; };
@@ -1434,20 +1419,22 @@ static bool plan_stream_lists(const stwq_linear_problem* problems, int count, lo
 }
 
 // problems: host descriptors of a grouped launch (nullptr for a single problem); plan.v[0 .. count) holds the processing order.
+template <class C>
 static int launch_stream(const stwq::LinearArgs& single, const stwq_linear_problem* problems, const stwq_linear_problem* problems_dev,
                          int count, long long n_tiles, stwq::GroupPlan& plan, hipStream_t s) {
     using namespace stwq;
-    typedef StreamDecodeCfg C;
     constexpr int kLds = C::kOffTables + 2 * TileTables<C>::kBytes + (kMaxGroup + 1) * 4 + kPlanEntries * 2;
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
-    static const int attr = set_ring(linear_stream_kernel, kLds);
+    static_assert(C::kWgsPerCu * kLds <= 160 * 1024, "LDS of one CU");
+    static const int attr = set_ring(linear_stream_kernel<C>, kLds);
     if (attr != STWQ_OK) return attr;
     int cus = 0;
     const int rc = compute_units(&cus);
     if (rc != STWQ_OK) return rc;
-    const long long grid = n_tiles < cus ? n_tiles : cus;
-    const bool planned = problems && n_tiles > grid && plan_stream_lists(problems, count, n_tiles, static_cast<int>(grid), plan);
-    linear_stream_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), kLds, s>>>(single, problems_dev, count, n_tiles,
+    const long long slots = static_cast<long long>(cus) * C::kWgsPerCu;
+    const long long grid = n_tiles < slots ? n_tiles : slots;
+    const bool planned = problems && n_tiles > grid && plan_stream_lists<C>(problems, count, n_tiles, static_cast<int>(grid), plan);
+    linear_stream_kernel<C><<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), kLds, s>>>(single, problems_dev, count, n_tiles,
                                                                                            planned ? 1 : 0, plan);
     return launch_status("linear_stream_kernel");
 }
@@ -1491,7 +1478,7 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
         const long long n_tiles = ((M + C::kTileM - 1) / C::kTileM) * ((p.N + C::kTileO - 1) / C::kTileO);
         STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
         static GroupPlan no_plan = {};
-        return launch_stream(p, nullptr, nullptr, 0, n_tiles, no_plan, s);
+        return launch_stream<C>(p, nullptr, nullptr, 0, n_tiles, no_plan, s);
     }
     if (schedule == STWQ_SCHEDULE_GENERIC) {
         const long long gx = (M + 63) / 64;
@@ -1543,7 +1530,7 @@ extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int coun
     if (streaming) {
         GroupPlan plan;
         std::copy(order.begin(), order.end(), plan.v);
-        return launch_stream(LinearArgs{}, problems, problems_dev, count, n_tiles, plan, static_cast<hipStream_t>(stream));
+        return launch_stream<StreamDecodeCfg>(LinearArgs{}, problems, problems_dev, count, n_tiles, plan, static_cast<hipStream_t>(stream));
     }
     GroupOrder go = {};
     std::copy(order.begin(), order.end(), go.v);

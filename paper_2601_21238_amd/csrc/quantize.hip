@@ -64,21 +64,71 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     quantize_rows(x, M, K, L, inv_s, inv_delta, zp, qmax, off, q, static_cast<long long>(blockIdx.x) * kQuantRows);
 }
 
-// Grouped form: block b belongs to the problem whose run of ceil(M / kQuantRows) blocks contains b.
-// The block counts are fetched by all threads at once (one round trip to memory, not one per
-// problem); the walk over them then runs on LDS.
+// Grouped form for many small problems (a decode step quantizes about a hundred rows for each of its
+// linears).  A block takes kGroupRows consecutive rows of one problem and walks them as ONE flat list of
+// 16-byte groups, four loads in flight per thread, so that rows shorter than the block keep every thread
+// busy; the rows' parameters sit in LDS.  Block b belongs to the problem whose run of
+// ceil(M / kGroupRows) blocks contains b: the block counts are fetched by all threads at once, summed by a
+// wave-wide scan and searched by bisection, all on LDS (a thread walking the list would spend longer on
+// that than on its rows).
 constexpr int kQuantMaxGroup = 1024;
+constexpr int kGroupRows = 8;
+constexpr int kGroupLoads = 4;
 __global__ __launch_bounds__(kQuantThreads) void quantize_grouped_kernel(const stwq_quantize_problem* __restrict__ problems, int count) {
-    __shared__ int nblocks[kQuantMaxGroup];
-    for (int i = threadIdx.x; i < count; i += kQuantThreads) nblocks[i] = (problems[i].M + kQuantRows - 1) / kQuantRows;
+    __shared__ int prefix[kQuantMaxGroup + 1];
+    __shared__ float row_id[kGroupRows], row_z[kGroupRows];
+    for (int i = threadIdx.x; i < count; i += kQuantThreads) prefix[i + 1] = (problems[i].M + kGroupRows - 1) / kGroupRows;
     __syncthreads();
-    int b = blockIdx.x, i = 0;
-    while (i < count && b >= nblocks[i]) b -= nblocks[i++];
-    if (i == count) return;
-    const stwq_quantize_problem& p = problems[i];
+    running_counts(prefix, count);
+    __syncthreads();
+    const int b = blockIdx.x;
+    int lo = 0, hi = count;                        // the problem i with prefix[i] <= b < prefix[i + 1]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= b) lo = mid; else hi = mid;
+    }
+    const stwq_quantize_problem& p = problems[lo];
+    const long long m0 = static_cast<long long>(b - prefix[lo]) * kGroupRows;
+    const int M = p.M, K = p.K, L = p.L;
+    const int rows = static_cast<int>(min(static_cast<long long>(kGroupRows), M - m0));
+    if (threadIdx.x < rows) {
+        const int t = static_cast<int>((m0 + threadIdx.x) % L);
+        row_id[threadIdx.x] = p.inv_delta_dev[t];
+        row_z[threadIdx.x] = static_cast<float>(p.zp_dev[t]);
+    }
+    __syncthreads();
     const float qmax = static_cast<float>((1 << p.a_bits) - 1);
-    quantize_rows(p.x_dev, p.M, p.K, p.L, p.inv_s_dev, p.inv_delta_dev, p.zp_dev, qmax, p.a_bits == 8 ? 128 : 0, p.q_dev,
-                  static_cast<long long>(b) * kQuantRows);
+    const int off = p.a_bits == 8 ? 128 : 0;
+    const int k4n = K >> 2, total = rows * k4n;    // the rows are consecutive in memory: group e is float4 number e from row m0 on
+    const f4* x4 = reinterpret_cast<const f4*>(p.x_dev + m0 * K);
+    const float4* s4 = reinterpret_cast<const float4*>(p.inv_s_dev);
+    uint32_t* q4 = reinterpret_cast<uint32_t*>(p.q_dev + m0 * K);
+    for (int e0 = threadIdx.x; e0 < total; e0 += kGroupLoads * kQuantThreads) {
+        f4 v[kGroupLoads];
+#pragma unroll
+        for (int u = 0; u < kGroupLoads; ++u) {
+            const int e = min(e0 + u * kQuantThreads, total - 1);      // past the end: a valid group, not stored
+            v[u] = __builtin_nontemporal_load(x4 + e);
+        }
+#pragma unroll
+        for (int u = 0; u < kGroupLoads; ++u) {
+            const int e = e0 + u * kQuantThreads;
+            if (e >= total) break;
+            const int r = e / k4n, k4 = e - r * k4n;
+            f4 pre = v[u];
+            if (s4) {
+                const float4 sv = s4[k4];
+                pre.x *= sv.x; pre.y *= sv.y; pre.z *= sv.z; pre.w *= sv.w;
+            }
+            const float id = row_id[r], zf = row_z[r];
+            const int a = quant_code(pre.x, id, zf, qmax) - off;
+            const int bb = quant_code(pre.y, id, zf, qmax) - off;
+            const int c = quant_code(pre.z, id, zf, qmax) - off;
+            const int d = quant_code(pre.w, id, zf, qmax) - off;
+            q4[e] = (static_cast<uint32_t>(a) & 0xFFu) | ((static_cast<uint32_t>(bb) & 0xFFu) << 8) |
+                    ((static_cast<uint32_t>(c) & 0xFFu) << 16) | (static_cast<uint32_t>(d) << 24);
+        }
+    }
 }
 
 }  // namespace stwq
@@ -107,7 +157,7 @@ extern "C" int stwq_quantize_act_grouped(const stwq_quantize_problem* problems, 
         const int rc = check_quantize_args("stwq_quantize_act_grouped", p.x_dev, p.M, p.K, p.L, p.inv_s_dev, p.inv_delta_dev,
                                            p.zp_dev, p.a_bits, p.q_dev);
         if (rc != STWQ_OK) return rc;
-        blocks += (static_cast<long long>(p.M) + kQuantRows - 1) / kQuantRows;
+        blocks += (static_cast<long long>(p.M) + kGroupRows - 1) / kGroupRows;
     }
     STWQ_REQUIRE(blocks <= 0x7FFFFFFFLL, "stwq_quantize_act_grouped: too many rows");
     quantize_grouped_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kQuantThreads), 0, static_cast<hipStream_t>(stream)>>>(
