@@ -489,7 +489,9 @@ __device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int 
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 settle(v[u]);
-                if (o_ok && mbase + (r0 + u) * kRowsPerRead < p.M) ybase[(r0 + u) * row_step] = __builtin_bit_cast(u4, v[u]);
+                // non-temporal: the output is not read again here, and should not push operand tiles out of the L2
+                if (o_ok && mbase + (r0 + u) * kRowsPerRead < p.M)
+                    __builtin_nontemporal_store(__builtin_bit_cast(u4, v[u]), ybase + (r0 + u) * row_step);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -1031,7 +1033,7 @@ __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m
 #pragma unroll
         for (int u = 0; u < kReads; ++u) {
             settle(v[u]);
-            if (o_ok && mbase + u * kRowsPerRead < p.M) ybase[u * row_step] = __builtin_bit_cast(u4, v[u]);
+            if (o_ok && mbase + u * kRowsPerRead < p.M) __builtin_nontemporal_store(__builtin_bit_cast(u4, v[u]), ybase + u * row_step);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
