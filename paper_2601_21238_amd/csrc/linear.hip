@@ -1368,10 +1368,47 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
     return launch_status("linear_prefill_kernel");
 }
 
-// Tile lists for a grouped streaming launch: tiles in processing order (cost non-increasing) each go to the
-// workgroup with the least work so far.  The cost of a tile is its K stages plus the epilogue and tile
+// Tile lists for a grouped streaming launch.  The cost of a tile is its K stages plus the epilogue and tile
 // switch, measured at 3.4 stages' worth (the output tile is a quarter of the bytes of an 11-stage tile's
-// weights).  Returns false when the lists do not fit the plan.
+// weights).  Tiles in processing order (cost non-increasing) each go to the workgroup with the least work
+// so far, among the workgroups `owner` allows for the tile's problem.
+struct StreamLists {
+    std::vector<std::vector<uint16_t>> tiles;    // per workgroup, increasing ids
+    long long longest = 0;                       // work of the busiest workgroup
+};
+template <class C>
+static StreamLists deal_stream_tiles(const stwq_linear_problem* problems, const uint16_t* order, int count, int grid,
+                                     int groups, const std::vector<int>& owner) {
+    // workgroup g belongs to group g % groups; owner[i] is the group of the problem at position i of the order
+    typedef std::pair<long long, int> Load;                       // (work so far, workgroup)
+    std::vector<std::priority_queue<Load, std::vector<Load>, std::greater<Load>>> least(groups);
+    for (int g = 0; g < grid; ++g) least[g % groups].push(Load(0, g));
+    StreamLists r;
+    r.tiles.resize(grid);
+    int tile = 0;
+    for (int i = 0; i < count; ++i) {
+        const stwq_linear_problem& q = problems[order[i]];
+        const int tiles = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+        const long long cost = 5LL * ((q.K + C::BK - 1) / C::BK) + 17;
+        auto& heap = least[owner[i]];
+        for (int t = 0; t < tiles; ++t, ++tile) {
+            Load l = heap.top();
+            heap.pop();
+            r.tiles[l.second].push_back(static_cast<uint16_t>(tile));
+            l.first += cost;
+            r.longest = std::max(r.longest, l.first);
+            heap.push(l);
+        }
+    }
+    return r;
+}
+
+// Fills plan.v after the processing order (plan.v[0 .. count)) with the per-workgroup tile lists.  Two ways of
+// dealing are tried.  (1) Whole problems are given to one XCD each (workgroup ids go to the 8 XCDs in turn;
+// largest problem first to the XCD with the least work), and dealt among that XCD's workgroups: all
+// tiles of a problem then read its activation rows through ONE L2, at about the same time.  (2) Every tile
+// may go to any workgroup.  (1) is taken unless it leaves the busiest workgroup with over 3 % more work
+// than (2).  Returns false when the lists do not fit the plan.
 template <class C>
 static bool plan_stream_lists(const stwq_linear_problem* problems, int count, long long n_tiles, int grid, stwq::GroupPlan& plan) {
     using namespace stwq;
@@ -1388,29 +1425,33 @@ static bool plan_stream_lists(const stwq_linear_problem* problems, int count, lo
         plan = last_plan;
         return true;
     }
-    std::vector<std::vector<uint16_t>> lists(grid);
-    typedef std::pair<long long, int> Load;                       // (work so far, workgroup)
-    std::priority_queue<Load, std::vector<Load>, std::greater<Load>> least;
-    for (int g = 0; g < grid; ++g) least.push(Load(0, g));
-    int tile = 0;
-    for (int i = 0; i < count; ++i) {
-        const stwq_linear_problem& q = problems[plan.v[i]];
-        const int tiles = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
-        const long long cost = 5LL * ((q.K + C::BK - 1) / C::BK) + 17;
-        for (int t = 0; t < tiles; ++t, ++tile) {
-            Load l = least.top();
-            least.pop();
-            lists[l.second].push_back(static_cast<uint16_t>(tile));
-            l.first += cost;
-            least.push(l);
+    StreamLists lists = deal_stream_tiles<C>(problems, plan.v, count, grid, 1, std::vector<int>(count, 0));
+    constexpr int kXcds = 8;
+    if (grid % kXcds == 0) {
+        std::vector<long long> work(count);
+        std::vector<int> by_work(count), owner(count);
+        for (int i = 0; i < count; ++i) {
+            const stwq_linear_problem& q = problems[plan.v[i]];
+            work[i] = static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO) *
+                      (5LL * ((q.K + C::BK - 1) / C::BK) + 17);
+            by_work[i] = i;
         }
+        std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return work[a] > work[b]; });
+        long long xcd_work[kXcds] = {};
+        for (int i : by_work) {
+            const int x = static_cast<int>(std::min_element(xcd_work, xcd_work + kXcds) - xcd_work);
+            owner[i] = x;
+            xcd_work[x] += work[i];
+        }
+        StreamLists local = deal_stream_tiles<C>(problems, plan.v, count, grid, kXcds, owner);
+        if (local.longest * 100 <= lists.longest * 103) lists = std::move(local);
     }
     uint16_t* start = plan.v + count;
     uint16_t* out = start + grid + 1;
     int n = 0;
     for (int g = 0; g < grid; ++g) {
         start[g] = static_cast<uint16_t>(n);
-        for (uint16_t t : lists[g]) out[n++] = t;
+        for (uint16_t t : lists.tiles[g]) out[n++] = t;
     }
     start[grid] = static_cast<uint16_t>(n);
     last_key.resize(count);
