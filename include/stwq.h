@@ -204,8 +204,10 @@ typedef struct stwq_linear_problem {
 
 /* Grouped form of stwq_linear for steps made of many small independent linears (an autoregressive
  * decode step streams every layer's weights once against about a hundred rows): all problems run
- * in ONE launch (the STREAM schedule when every K allows it, else DECODE), so that launch latency does
- * not hide the weight stream.
+ * in ONE launch, so that launch latency does not hide the weight stream.  A group with packed weights
+ * runs on the streaming kernel (a row-major problem may be mixed in), a group of row-major weights on
+ * the tiled DECODE schedule.  The work is balanced over the compute units on the host, from the shapes
+ * (cached per calling thread while the shapes repeat).
  *   problems      HOST array of count descriptors (read during the call only: validation and grid size);
  *   problems_dev  DEVICE copy of the same count descriptors, made by the caller, 8-byte aligned; the
  *                 kernel reads it, so it must stay unchanged until the stream has passed this call.
