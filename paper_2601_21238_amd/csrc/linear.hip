@@ -808,10 +808,11 @@ struct StreamCfg {
     static constexpr int kWaveStage = 32 * TI * 64;       // output staging: 32 rows x 64 channels of bf16
     static constexpr int kJPerPass = 1;
     static constexpr int kOffStaging = kRing, kOffTables = kRing + kWaves * kWaveStage;
-    // Ring wait in the steady state: operations issued after the awaited stage's ring loads.  A stage is
-    // requested as W(all k-steps but the last) | X x kLoadsX | W(last k-step); awaited are the X loads of the stage after the
-    // current one.  One less than the count, in case the compiler swaps a weight load with a ring load.
-    static constexpr int kWaitSteady = TI + kOps * (D - 2) + TI * (kKS - 1) - 1;
+    // Ring wait in the steady state: operations issued after the awaited stage's ring loads.  In the stage loop a
+    // stage is requested as W(all but the last load) | X x kLoadsX | W(the last load), at the start as W(all k-steps but
+    // the last) | X x kLoadsX | W(last k-step); awaited are the X loads of the stage after the current one.  One less
+    // than the count, in case the compiler swaps a weight load with a ring load.
+    static constexpr int kWaitSteady = 1 + kOps * (D - 2) + TI * (kKS - 1) - 1;
     static constexpr int kWaitFirst = TI + kOps * (D - 1) - 1;
     static_assert(D >= 2 && kWaitFirst <= 63, "vmcnt is a 6-bit counter");
 };
@@ -916,7 +917,7 @@ __device__ __forceinline__ void stream_tables(const StreamTile<C>& t, int8_t* ta
 // Where the stage requested now comes from: a tile and a stage in it, or nowhere (past the tile list).
 template <class C>
 struct StreamSrc {
-    const int8_t* w[C::TI];
+    const int8_t* w[C::TI];   // this lane's weight operands of the stage's first k-step
     const int8_t* xbase;
     unsigned xbytes;
     unsigned xoff;
@@ -933,21 +934,22 @@ __device__ __forceinline__ StreamSrc<C> stream_source(const StreamTile<C>& cur, 
     const int nk = in_cur ? cur.nk : nxt.nk;
     const int tail = in_cur ? cur.tail_ks : nxt.tail_ks;
     const bool real = in_cur || more;             // otherwise: past the end of the tile list
+    r.kstep = real ? tt * C::kKS : 0;             // nobody consumes an unreal stage: its ring loads re-read the tile's first bytes
+    r.kstep_stride = in_cur ? cur.kstep_stride : nxt.kstep_stride;
+    const long long first = static_cast<long long>(r.kstep) * r.kstep_stride;     // uniform
 #pragma unroll
-    for (int i = 0; i < C::TI; ++i) r.w[i] = in_cur ? cur.w[i] : nxt.w[i];
+    for (int i = 0; i < C::TI; ++i) r.w[i] = (in_cur ? cur.w[i] : nxt.w[i]) + first;
     r.xbase = (in_cur || !more) ? cur.xbase : nxt.xbase;
     r.xbytes = (in_cur || !more) ? cur.xbytes : nxt.xbytes;
     r.xoff = (in_cur || !more) ? cur.xoff : nxt.xoff;
     r.K = (in_cur || !more) ? cur.p.K : nxt.p.K;
-    r.kstep = real ? tt * C::kKS : 0;             // nobody consumes an unreal stage: its ring loads re-read the tile's first bytes
-    r.kstep_stride = in_cur ? cur.kstep_stride : nxt.kstep_stride;
     r.valid_ks = real ? ((tail != 0 && tt == nk - 1) ? tail : C::kKS) : 0;
     return r;
 }
 // The weight operand i of k-step ks of the requested stage (zeros where the stage has no such k-step).
 template <class C>
 __device__ __forceinline__ v4i stream_load_w(const StreamSrc<C>& r, int ks, int i) {
-    const int8_t* a = r.w[i] + static_cast<long long>(r.kstep + ks) * r.kstep_stride;
+    const int8_t* a = r.w[i] + ks * r.kstep_stride;
     if (ks >= r.valid_ks) a = reinterpret_cast<const int8_t*>(kZeros);
     // A global (not flat) load, tracked by the compiler.  Non-temporal: every weight byte is read once, and kept out
     // of the way it leaves the L2 to the activation rows, which all workgroups of a problem read.
@@ -964,6 +966,15 @@ __device__ __forceinline__ void stream_load_x(const StreamSrc<C>& r, int8_t* slo
                                                  r.xoff + static_cast<unsigned>(u * C::kWaves * C::kRowsPerLoad * r.K + r.kstep * 32), 0, 0, 0);
 }
 
+template <class C>
+__device__ __forceinline__ v4i lds_read16_at(unsigned addr, int j) {      // operand of the j-th 32-row tile
+    switch (j) {
+        case 0: return lds_read16<0>(addr);
+        case 1: return lds_read16<1 * 32 * C::BK>(addr);
+        case 2: return lds_read16<2 * 32 * C::BK>(addr);
+        default: return lds_read16<3 * 32 * C::BK>(addr);
+    }
+}
 template <class C, int... J>
 __device__ __forceinline__ void stream_read_b(unsigned addr, v4i (&b)[sizeof...(J)], std::integer_sequence<int, J...>) {
     ((b[J] = lds_read16<J * 32 * C::BK>(addr)), ...);
@@ -978,6 +989,14 @@ __device__ __forceinline__ void stream_consts(unsigned cbase, v4i (&dwv)[sizeof.
     typedef TileTables<C> T;
     ((dwv[CH] = lds_ld16<T::kDw + 32 * CH>(cbase)), ...);
     ((bv[CH] = lds_ld16<T::kBias + 32 * CH>(cbase)), ...);
+}
+// An accumulator element as a vector register.  The accumulators live in the accumulation registers for the MFMAs;
+// reading them there, by name, keeps the copies on this path (left to itself the compiler may copy every MFMA's
+// result to vector registers right after the MFMA, in the stage loop).
+__device__ __forceinline__ int from_acc(int a) {
+    int v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
 }
 template <class C>
 __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], unsigned stage,
@@ -1012,10 +1031,10 @@ __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m
 #pragma unroll
         for (int c = 0; c < OC; ++c) {           // c = 4 i + g: channels (wave TI + i) 32 + 8 g + 4 hi .. + 3
             const int i = c >> 2, g = c & 3;
-            const float y0 = fmaf(static_cast<float>(acc[i][j][4 * g]), dt[j] * __int_as_float(dwv[c][0]), __int_as_float(bv[c][0]));
-            const float y1 = fmaf(static_cast<float>(acc[i][j][4 * g + 1]), dt[j] * __int_as_float(dwv[c][1]), __int_as_float(bv[c][1]));
-            const float y2 = fmaf(static_cast<float>(acc[i][j][4 * g + 2]), dt[j] * __int_as_float(dwv[c][2]), __int_as_float(bv[c][2]));
-            const float y3 = fmaf(static_cast<float>(acc[i][j][4 * g + 3]), dt[j] * __int_as_float(dwv[c][3]), __int_as_float(bv[c][3]));
+            const float y0 = fmaf(static_cast<float>(from_acc(acc[i][j][4 * g])), dt[j] * __int_as_float(dwv[c][0]), __int_as_float(bv[c][0]));
+            const float y1 = fmaf(static_cast<float>(from_acc(acc[i][j][4 * g + 1])), dt[j] * __int_as_float(dwv[c][1]), __int_as_float(bv[c][1]));
+            const float y2 = fmaf(static_cast<float>(from_acc(acc[i][j][4 * g + 2])), dt[j] * __int_as_float(dwv[c][2]), __int_as_float(bv[c][2]));
+            const float y3 = fmaf(static_cast<float>(from_acc(acc[i][j][4 * g + 3])), dt[j] * __int_as_float(dwv[c][3]), __int_as_float(bv[c][3]));
             u2 out = {pack_bf16(y0, y1), pack_bf16(y2, y3)};
             lds_st8(stage_lane ^ (c * 16), out);
         }
@@ -1140,35 +1159,53 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
             unsigned cur_b = lds_base + d * C::kOpX + offB;
             unsigned nxt_b = lds_base + ((d + 1) % D) * C::kOpX + offB;
             asm volatile("" : "+v"(cur_b), "+v"(nxt_b));   // keeps the per-k-step addresses out of loop-invariant registers
-            const StreamSrc<C> src = stream_source<C>(cur, nxt, more, done, s + D);   // the stage requested now
+            // One wave per SIMD issues in order: whatever stands between two MFMAs runs in the shadow of the first
+            // (32 cycles each), whatever stands after a run of them waits for the whole run.  So the k-step's
+            // other work is dealt out between its eight MFMAs, and the order is pinned.
+            StreamSrc<C> src;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                if (ks < KS - 1) {
-                    // one wave per SIMD: the next k-step's operands are read under this k-step's MFMAs
-                    stream_read_b<C>(cur_b ^ ((ks + 1) * 32), b[(ks + 1) & 1], std::make_integer_sequence<int, TJ>{});
-                    wait_lgkm<TJ>();
-                } else {
-                    // Once this stage's last operands are in registers every wave is done with its ring slot; the
-                    // ring loads of the next stage must have landed before anyone reads them.
-                    wait_vm<C::kWaitSteady>();
-                    wait_lgkm<0>();
-                    __builtin_amdgcn_s_barrier();
-                    asm volatile("" ::: "memory");
-                    stream_read_b<C>(nxt_b, b[0], std::make_integer_sequence<int, TJ>{});
+                constexpr int kHalf = TI * TJ / 2;
+                const bool last = ks == KS - 1;
+                v4i (&bc)[TJ] = b[ks & 1];
+                v4i (&bn)[TJ] = b[(ks + 1) & 1];
+                // this k-step's operands were read under the previous k-step's MFMAs
+                if (last) wait_vm<C::kWaitSteady>();   // ... and the ring loads of the next stage have landed (this wave's)
+                wait_lgkm<0>();
+#pragma unroll
+                for (int j = 0; j < TJ; ++j) settle(bc[j]);
+#pragma unroll
+                for (int n = 0; n < TI * TJ; ++n) {
+                    const int i = n / TJ, j = n % TJ;
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[d][ks][i], bc[j], acc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (ks == 0 && n == 0) {
+                        src = stream_source<C>(cur, nxt, more, done, s + D);   // the stage requested now
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (!last) {
+                        if (n < TJ) bn[n] = lds_read16_at<C>(cur_b ^ ((ks + 1) * 32), n);
+                    } else {
+                        // Once this stage's last operands are in registers every wave is done with its ring slot; the
+                        // ring loads of the next stage must have landed before anyone reads them.
+                        if (n == kHalf - 1) {
+                            __builtin_amdgcn_s_barrier();
+                            asm volatile("" ::: "memory");
+                        }
+                        if (n >= kHalf && n < kHalf + TJ) bn[n - kHalf] = lds_read16_at<C>(nxt_b, n - kHalf);
+                    }
+                    // weight registers of tile i are free once its last MFMA has been issued
+                    if (j == TJ - 1 && !(last && i == TI - 1)) {
+                        wreg[d][ks][i] = stream_load_w<C>(src, ks, i);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                if (last) {
                     if (s + D == cur.nk && more) stream_tables<C>(nxt, smem + C::kOffTables + (tb ^ 1) * T::kBytes, wave, lane);
                     stream_load_x<C>(src, smem + d * C::kOpX, wave);
                     __builtin_amdgcn_sched_barrier(0);
+                    wreg[d][ks][TI - 1] = stream_load_w<C>(src, ks, TI - 1);
                 }
-#pragma unroll
-                for (int j = 0; j < TJ; ++j) settle(b[ks & 1][j]);
-#pragma unroll
-                for (int i = 0; i < TI; ++i)
-#pragma unroll
-                    for (int j = 0; j < TJ; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[d][ks][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int i = 0; i < TI; ++i) wreg[d][ks][i] = stream_load_w<C>(src, ks, i);   // this k-step's registers are free again
                 __builtin_amdgcn_sched_barrier(0);
             }
 
@@ -1188,8 +1225,8 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
                             for (int g = 0; g < 4; ++g) {
                                 const int o4 = cur.o0 + (wave * TI + i) * 32 + 8 * g + 4 * hi;
                                 if (m < p.M && o4 < p.N) {   // a global (not flat) store: a flat one would make every later wait vmcnt(0)
-                                    const v4i raw = {acc[i][j][4 * g] - start[i][j][4 * g], acc[i][j][4 * g + 1] - start[i][j][4 * g + 1],
-                                                     acc[i][j][4 * g + 2] - start[i][j][4 * g + 2], acc[i][j][4 * g + 3] - start[i][j][4 * g + 3]};
+                                    const v4i raw = {from_acc(acc[i][j][4 * g]) - start[i][j][4 * g], from_acc(acc[i][j][4 * g + 1]) - start[i][j][4 * g + 1],
+                                                     from_acc(acc[i][j][4 * g + 2]) - start[i][j][4 * g + 2], from_acc(acc[i][j][4 * g + 3]) - start[i][j][4 * g + 3]};
                                     *(global_v4i*)(p.acc_dbg + m * p.N + o4) = raw;
                                 }
                             }
