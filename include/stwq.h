@@ -216,6 +216,16 @@ typedef struct stwq_linear_problem {
 STWQ_API int stwq_linear_grouped(const stwq_linear_problem* problems, int count,
                                  const stwq_linear_problem* problems_dev, void* stream);
 
+/* Diagnostic, host only (no GPU call, pointers in the descriptors are not used): the work lists from which a
+ * grouped launch of these shapes on packed weights would run on a device with `workgroups` workgroup slots (one
+ * per compute unit).  Tiles are 256 channels x 128 rows, numbered along the problems in processing order
+ * (order_out[count]: longest K first), channel tiles fastest within a problem; workgroup g runs
+ * tiles_out[starts_out[g] .. starts_out[g + 1]) in that order (starts_out has workgroups + 1 entries).
+ * Returns the number of tiles, 0 when the launch would deal the tiles out in turn instead (fewer tiles than
+ * workgroups, or lists that do not fit the kernel arguments), or a negative status. */
+STWQ_API int stwq_linear_grouped_plan(const stwq_linear_problem* problems, int count, int workgroups,
+                                      uint16_t* order_out, uint16_t* starts_out, uint16_t* tiles_out, int tiles_capacity);
+
 #ifdef __cplusplus
 }
 #endif

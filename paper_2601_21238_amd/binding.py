@@ -22,7 +22,8 @@ LAYOUT_ROWMAJOR, LAYOUT_PANEL32 = 0, 1
 
 EXPORTS = ("stwq_last_error", "stwq_version", "stwq_calibrate_stats", "stwq_finalize_act_params",
            "gps_workspace_bytes", "gps_solve_scale", "gps_fold_weights", "stwq_quantize_act", "stwq_quantize_act_grouped",
-           "stwq_linear", "stwq_linear_ex", "stwq_packed_weight_bytes", "stwq_pack_weights", "stwq_linear_grouped")
+           "stwq_linear", "stwq_linear_ex", "stwq_packed_weight_bytes", "stwq_pack_weights", "stwq_linear_grouped",
+           "stwq_linear_grouped_plan")
 
 
 class LinearProblem(C.Structure):
@@ -85,6 +86,8 @@ def lib() -> C.CDLL:
     l.stwq_packed_weight_bytes.argtypes = [i32, i32]
     l.stwq_pack_weights.restype = i32
     l.stwq_pack_weights.argtypes = [vp, i32, i32, vp, vp]
+    l.stwq_linear_grouped_plan.restype = i32
+    l.stwq_linear_grouped_plan.argtypes = [vp, i32, i32, vp, vp, vp, i32]
     l.stwq_linear_grouped.restype = i32
     l.stwq_linear_grouped.argtypes = [vp, i32, vp, vp]
     _lib = l
@@ -211,6 +214,28 @@ def stwq_pack_weights(wq, packed) -> None:
     if packed.dtype != torch.int8 or not packed.is_cuda or not packed.is_contiguous() or packed.numel() != stwq_packed_weight_bytes(N, K):
         raise ValueError("packed must be a contiguous int8 device tensor of stwq_packed_weight_bytes(N, K) bytes")
     _check(lib().stwq_pack_weights(_dev(wq, torch.int8, None, "wq"), N, K, packed.data_ptr(), _stream(wq)))
+
+
+def stwq_linear_grouped_plan(shapes, workgroups: int):
+    """Host-only diagnostic: (order, lists) for a grouped launch of problems with the given (M, K, N) shapes on packed
+    weights; lists[g] holds workgroup g's tile ids, or lists is None when the launch would deal tiles out in turn."""
+    count = len(shapes)
+    host = (LinearProblem * count)()
+    tiles = 0
+    for h, (M, K, N) in zip(host, shapes):
+        h.M, h.K, h.N, h.L, h.a_bits, h.w_layout = M, K, N, 1, 8, LAYOUT_PANEL32
+        tiles += ((M + 127) // 128) * ((N + 255) // 256)
+    order = np.zeros(count, np.uint16)
+    starts = np.zeros(workgroups + 1, np.uint16)
+    out = np.zeros(max(tiles, 1), np.uint16)
+    n = lib().stwq_linear_grouped_plan(C.addressof(host), count, workgroups, order.ctypes.data, starts.ctypes.data,
+                                       out.ctypes.data, out.size)
+    if n < 0:
+        _check(n)
+    if n == 0:
+        return order, None
+    used = min(workgroups, tiles)
+    return order, [out[starts[g]:starts[g + 1]].tolist() for g in range(used)]
 
 
 class LinearGroup:

@@ -1617,6 +1617,32 @@ extern "C" int stwq_linear_grouped(const stwq_linear_problem* problems, int coun
     return launch_decode(LinearArgs{}, problems_dev, count, n_tiles, go, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int stwq_linear_grouped_plan(const stwq_linear_problem* problems, int count, int workgroups,
+                                        uint16_t* order_out, uint16_t* starts_out, uint16_t* tiles_out, int tiles_capacity) {
+    using namespace stwq;
+    typedef StreamDecodeCfg C;
+    clear_error();
+    STWQ_REQUIRE(problems && order_out && starts_out && tiles_out, "stwq_linear_grouped_plan: null pointer");
+    STWQ_REQUIRE(count > 0 && count <= kMaxGroup, "stwq_linear_grouped_plan: count = %d must be in 1 .. %d", count, kMaxGroup);
+    STWQ_REQUIRE(workgroups > 0, "stwq_linear_grouped_plan: workgroups = %d", workgroups);
+    long long n_tiles = 0;
+    for (int i = 0; i < count; ++i) {
+        const stwq_linear_problem& q = problems[i];
+        STWQ_REQUIRE(q.M > 0 && q.N > 0 && q.K > 0, "stwq_linear_grouped_plan: problem %d has M = %d, K = %d, N = %d", i, q.M, q.K, q.N);
+        n_tiles += static_cast<long long>((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+    }
+    GroupPlan plan;
+    for (int i = 0; i < count; ++i) plan.v[i] = static_cast<uint16_t>(i);
+    std::stable_sort(plan.v, plan.v + count, [&](uint16_t a, uint16_t b) { return problems[a].K > problems[b].K; });
+    std::copy(plan.v, plan.v + count, order_out);
+    const long long grid = n_tiles < workgroups ? n_tiles : workgroups;
+    if (n_tiles <= grid || !plan_stream_lists<C>(problems, count, n_tiles, static_cast<int>(grid), plan)) return 0;
+    STWQ_REQUIRE(n_tiles <= tiles_capacity, "stwq_linear_grouped_plan: %lld tiles, room for %d", n_tiles, tiles_capacity);
+    std::copy(plan.v + count, plan.v + count + grid + 1, starts_out);
+    std::copy(plan.v + count + grid + 1, plan.v + count + grid + 1 + n_tiles, tiles_out);
+    return static_cast<int>(n_tiles);
+}
+
 extern "C" int stwq_pack_weights(const int8_t* wq_dev, int N, int K, int8_t* packed_dev, void* stream) {
     using namespace stwq;
     clear_error();
