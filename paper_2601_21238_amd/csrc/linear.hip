@@ -163,6 +163,7 @@ struct TileCfg {
     static constexpr int kLoadsX = kTileM / 16 / kWaves;
     static constexpr int kLoads = kLoadsW + kLoadsX;
     static constexpr int kChunks = TI * 4;                // 16-byte bf16 chunks per staged output row
+    static constexpr bool kAgprAcc = TI * TJ * 16 > 128;  // one wave per SIMD: the accumulators fill the accumulation registers
     static constexpr int kWaveStage = WAVE_STAGE_;        // bytes of LDS one wave stages its output through, per pass
     static constexpr int kJPerPass = kWaveStage / (32 * TI * 64);   // 32-token MFMA tiles staged per pass
     static_assert(kTileO % (16 * kWaves) == 0 && kTileM % (16 * kWaves) == 0, "tile rows must split over the waves");
@@ -409,22 +410,47 @@ __device__ __forceinline__ void init_acc(v16i (&acc)[C::TI][C::TJ], unsigned tab
 // writes them as bf16.  The values are transposed through `stage` (LDS private to the wave, 16-byte
 // XOR swizzle) so that the global stores are full row segments of 16 bytes per lane; TJ / JP passes
 // of JP token tiles each.  `stage` and `tab` are LDS addresses (this tile's tables).
+// An accumulator element as a vector register.  The accumulators live in the accumulation registers for the MFMAs;
+// reading them there, by name, keeps the copies on this path (left to itself the compiler may copy every MFMA's
+// result to vector registers right after the MFMA, in the stage loop).
+__device__ __forceinline__ int from_acc(int a) {
+    int v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+template <class C>
+__device__ __forceinline__ int acc_value(int a) {      // where the configuration's accumulators live
+    return C::kAgprAcc ? from_acc(a) : a;
+}
+// One 16-byte chunk of four output channels.  The per-channel constants are fetched kConstAhead chunks ahead
+// (LDS operations of a wave complete in order, so the wait counts the operations issued after this chunk's
+// two loads: the stores of the chunks in between and the loads of the chunks ahead).
+constexpr int kConstAhead = 2;
+template <class C, int CHUNK>
+__device__ __forceinline__ void epilogue_consts(unsigned cbase, v4i (&dwv)[C::kChunks], v4i (&bv)[C::kChunks]) {
+    typedef TileTables<C> T;
+    if (CHUNK < C::kChunks) {
+        constexpr int c = CHUNK < C::kChunks ? CHUNK : 0;
+        dwv[c] = lds_ld16<T::kDw + 32 * c>(cbase);
+        bv[c] = lds_ld16<T::kBias + 32 * c>(cbase);
+    }
+}
 template <class C, int CHUNK>
 __device__ __forceinline__ void epilogue_chunk(v16i (&acc)[C::TI][C::TJ], int pass, unsigned cbase, unsigned stage_lane,
-                                               const float (&dt)[C::TJ]) {
-    typedef TileTables<C> T;
-    constexpr int JP = C::kJPerPass, i = CHUNK >> 2, g = CHUNK & 3;
-    // the other wave of this SIMD covers the latency of these reads
-    v4i dwv = lds_ld16<T::kDw + 32 * CHUNK>(cbase), bv = lds_ld16<T::kBias + 32 * CHUNK>(cbase);
-    wait_lgkm<0>();
-    settle(dwv); settle(bv);
+                                               const float (&dt)[C::TJ], v4i (&dwv)[C::kChunks], v4i (&bv)[C::kChunks]) {
+    constexpr int JP = C::kJPerPass, OC = C::kChunks, i = CHUNK >> 2, g = CHUNK & 3;
+    epilogue_consts<C, CHUNK + kConstAhead>(cbase, dwv, bv);
+    constexpr int stores_between = JP * (CHUNK < kConstAhead ? CHUNK : kConstAhead);
+    constexpr int loads_ahead = 2 * ((OC - 1 - CHUNK) < kConstAhead ? (OC - 1 - CHUNK) : kConstAhead);
+    wait_lgkm<stores_between + loads_ahead>();
+    settle(dwv[CHUNK]); settle(bv[CHUNK]);
 #pragma unroll
     for (int jj = 0; jj < JP; ++jj) {
         const int j = pass * JP + jj;
-        const float y0 = fmaf(static_cast<float>(acc[i][j][4 * g]), dt[j] * __int_as_float(dwv[0]), __int_as_float(bv[0]));
-        const float y1 = fmaf(static_cast<float>(acc[i][j][4 * g + 1]), dt[j] * __int_as_float(dwv[1]), __int_as_float(bv[1]));
-        const float y2 = fmaf(static_cast<float>(acc[i][j][4 * g + 2]), dt[j] * __int_as_float(dwv[2]), __int_as_float(bv[2]));
-        const float y3 = fmaf(static_cast<float>(acc[i][j][4 * g + 3]), dt[j] * __int_as_float(dwv[3]), __int_as_float(bv[3]));
+        const float y0 = fmaf(static_cast<float>(acc_value<C>(acc[i][j][4 * g])), dt[j] * __int_as_float(dwv[CHUNK][0]), __int_as_float(bv[CHUNK][0]));
+        const float y1 = fmaf(static_cast<float>(acc_value<C>(acc[i][j][4 * g + 1])), dt[j] * __int_as_float(dwv[CHUNK][1]), __int_as_float(bv[CHUNK][1]));
+        const float y2 = fmaf(static_cast<float>(acc_value<C>(acc[i][j][4 * g + 2])), dt[j] * __int_as_float(dwv[CHUNK][2]), __int_as_float(bv[CHUNK][2]));
+        const float y3 = fmaf(static_cast<float>(acc_value<C>(acc[i][j][4 * g + 3])), dt[j] * __int_as_float(dwv[CHUNK][3]), __int_as_float(bv[CHUNK][3]));
         u2 out = {pack_bf16(y0, y1), pack_bf16(y2, y3)};
         // chunk c of row r sits at physical chunk c ^ (r & (chunks - 1)); stage_lane holds the lane's row and the
         // row's own permutation, so the chunk index enters as an XOR
@@ -435,7 +461,10 @@ __device__ __forceinline__ void epilogue_chunk(v16i (&acc)[C::TI][C::TJ], int pa
 template <class C, int... CH>
 __device__ __forceinline__ void epilogue_chunks(v16i (&acc)[C::TI][C::TJ], int pass, unsigned cbase, unsigned stage_lane,
                                                 const float (&dt)[C::TJ], std::integer_sequence<int, CH...>) {
-    (epilogue_chunk<C, CH>(acc, pass, cbase, stage_lane, dt), ...);
+    v4i dwv[C::kChunks], bv[C::kChunks];           // only the chunks in flight are live
+    // every LDS operation issued before this point has been waited for by the caller
+    ((CH < kConstAhead ? epilogue_consts<C, CH>(cbase, dwv, bv) : (void)0), ...);
+    (epilogue_chunk<C, CH>(acc, pass, cbase, stage_lane, dt, dwv, bv), ...);
 }
 
 template <class C, bool DRAIN = true>
@@ -582,8 +611,8 @@ __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem) {
                         const int o4 = o0 + wo * TI * 32 + i * 32 + 8 * g + 4 * hi;
                         if (m < p.M && o4 < p.N)
                             *reinterpret_cast<int4*>(p.acc_dbg + m * p.N + o4) =
-                                make_int4(acc[i][j][4 * g] - start[i][j][4 * g], acc[i][j][4 * g + 1] - start[i][j][4 * g + 1],
-                                          acc[i][j][4 * g + 2] - start[i][j][4 * g + 2], acc[i][j][4 * g + 3] - start[i][j][4 * g + 3]);
+                                make_int4(acc_value<C>(acc[i][j][4 * g]) - start[i][j][4 * g], acc_value<C>(acc[i][j][4 * g + 1]) - start[i][j][4 * g + 1],
+                                          acc_value<C>(acc[i][j][4 * g + 2]) - start[i][j][4 * g + 2], acc_value<C>(acc[i][j][4 * g + 3]) - start[i][j][4 * g + 3]);
                     }
             }
         }
@@ -801,6 +830,7 @@ struct StreamCfg {
     static constexpr int kChunks = TI * 4;                // 16-byte bf16 chunks per staged output row
     static constexpr int kOpX = kTileM * BK;              // one ring slot
     static constexpr int kRing = D * kOpX;
+    static constexpr bool kAgprAcc = WGS_ == 1;
     static constexpr int kRowsPerLoad = 1024 / BK;        // rows of one direct-to-LDS load (1 KB)
     static constexpr int kLoadsX = kOpX / 1024 / kWaves;  // direct-to-LDS loads per wave and stage
     static constexpr int kLoadsW = kKS * TI;              // weight loads per wave and stage
@@ -989,14 +1019,6 @@ __device__ __forceinline__ void stream_consts(unsigned cbase, v4i (&dwv)[sizeof.
     typedef TileTables<C> T;
     ((dwv[CH] = lds_ld16<T::kDw + 32 * CH>(cbase)), ...);
     ((bv[CH] = lds_ld16<T::kBias + 32 * CH>(cbase)), ...);
-}
-// An accumulator element as a vector register.  The accumulators live in the accumulation registers for the MFMAs;
-// reading them there, by name, keeps the copies on this path (left to itself the compiler may copy every MFMA's
-// result to vector registers right after the MFMA, in the stage loop).
-__device__ __forceinline__ int from_acc(int a) {
-    int v;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
-    return v;
 }
 template <class C>
 __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], unsigned stage,
