@@ -37,6 +37,7 @@ struct LinearArgs {
     uint16_t* y;
     int32_t* acc_dbg;
     int M, K, N, L, off;
+    int t0;              // token position of row 0 (rows m sit at position (t0 + m) mod L); 0 unless a launch is split by rows
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kSimpleThreads) void linear_simple_kernel(LinearArg
     // D layout of the 32 x 32 MFMA: lane holds column (lane % 32); register r holds row
     // 8 * (r / 4) + 4 * (lane / 32) + r % 4.
     if (!m_ok) return;
-    const int t = static_cast<int>(row_m % p.L);
+    const int t = static_cast<int>((row_m + p.t0) % p.L);
     const float dt = p.delta[t];
     const int zs = p.zp[t] - p.off;
 #pragma unroll
@@ -352,7 +353,7 @@ __device__ __forceinline__ void issue_tables(const LinearArgs& p, long long m0, 
     const int eo = e % C::kTileO, em = e % C::kTileM;
     const int o = min(o0 + eo, p.N - 1);
     const unsigned m = static_cast<unsigned>(min(m0 + em, static_cast<long long>(p.M) - 1));   // M < 2^31
-    const int tok = static_cast<int>(m % static_cast<unsigned>(p.L));
+    const int tok = static_cast<int>((m + static_cast<unsigned>(p.t0)) % static_cast<unsigned>(p.L));
     int8_t* dst_o = table + ((wave * 64) % C::kTileO) * 4;
     int8_t* dst_m = table + ((wave * 64) % C::kTileM) * 4;
     const float* bsrc = p.bias ? p.bias + o : reinterpret_cast<const float*>(kZeros) + lane;
@@ -708,6 +709,7 @@ __device__ __forceinline__ LinearArgs args_of(const stwq_linear_problem& q) {
     p.M = __builtin_amdgcn_readfirstlane(q.M); p.K = __builtin_amdgcn_readfirstlane(q.K);
     p.N = __builtin_amdgcn_readfirstlane(q.N); p.L = __builtin_amdgcn_readfirstlane(q.L);
     p.off = __builtin_amdgcn_readfirstlane(q.a_bits) == 8 ? 128 : 0;
+    p.t0 = 0;
     return p;
 }
 
@@ -931,7 +933,7 @@ __device__ __forceinline__ void stream_tables(const StreamTile<C>& t, int8_t* ta
     const int eo = e % C::kTileO, em = e % C::kTileM;
     const int o = min(t.o0 + eo, p.N - 1);
     const unsigned m = static_cast<unsigned>(min(t.m0 + em, static_cast<long long>(p.M) - 1));   // M < 2^31
-    const int tok = static_cast<int>(m % static_cast<unsigned>(p.L));
+    const int tok = static_cast<int>((m + static_cast<unsigned>(p.t0)) % static_cast<unsigned>(p.L));
     int8_t* dst_o = table + ((wave * 64) % C::kTileO) * 4;
     int8_t* dst_m = table + ((wave * 64) % C::kTileM) * 4;
     const unsigned nb = static_cast<unsigned>(p.N) * 4, lb = static_cast<unsigned>(p.L) * 4;
@@ -1557,10 +1559,34 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
         if (rc != STWQ_OK) return rc;
         bool narrow_tile = schedule == STWQ_SCHEDULE_PREFILL_NARROW;
         if (schedule == STWQ_SCHEDULE_PREFILL) {
-            // Rounds of one tile per CU; a narrow tile costs a little over half a wide one (measured: 0.55).
+            // Rounds of one tile per CU, in units of a wide tile's time; a narrow tile costs a little over half a
+            // wide one (measured: 0.57).  Three ways: all wide, all narrow, or the full rounds of wide tiles followed
+            // by a second launch that covers the remaining rows with narrow tiles (a last round of wide tiles that
+            // fills a third of the CUs costs a whole tile time; the same rows in narrow tiles cost 0.57).
+            constexpr double kNarrow = 0.57, kSecondLaunch = 0.08;
             const long long wide = prefill_tiles<PrefillCfg>(p), narrow = prefill_tiles<PrefillNarrowCfg>(p);
             const double t_wide = static_cast<double>((wide + cus - 1) / cus);
-            const double t_narrow = 0.55 * static_cast<double>((narrow + cus - 1) / cus);
+            const double t_narrow = kNarrow * static_cast<double>((narrow + cus - 1) / cus);
+            const long long tiles_o = (p.N + PrefillCfg::kTileO - 1) / PrefillCfg::kTileO, tiles_m = wide / tiles_o;
+            const long long full = wide / cus;                                  // full rounds of wide tiles
+            const long long rows_main = full * cus / tiles_o;                   // whole tile rows that fit them
+            if (rows_main > 0 && rows_main < tiles_m) {
+                const long long m1 = rows_main * PrefillCfg::kTileM;
+                LinearArgs rest = p;
+                rest.q += m1 * p.K;
+                rest.y += m1 * p.N;
+                if (rest.acc_dbg) rest.acc_dbg += m1 * p.N;
+                rest.M = static_cast<int>(M - m1);
+                rest.t0 = static_cast<int>((p.t0 + m1) % p.L);
+                const double t_split = static_cast<double>((rows_main * tiles_o + cus - 1) / cus) +
+                                       kNarrow * static_cast<double>((prefill_tiles<PrefillNarrowCfg>(rest) + cus - 1) / cus) + kSecondLaunch;
+                if (t_split < t_wide && t_split < t_narrow) {
+                    LinearArgs main = p;
+                    main.M = static_cast<int>(m1);
+                    const int rc1 = launch_prefill<PrefillCfg>(main, cus, s);
+                    return rc1 != STWQ_OK ? rc1 : launch_prefill<PrefillNarrowCfg>(rest, cus, s);
+                }
+            }
             narrow_tile = t_narrow < t_wide;
         }
         return narrow_tile ? launch_prefill<PrefillNarrowCfg>(p, cus, s) : launch_prefill<PrefillCfg>(p, cus, s);
