@@ -763,6 +763,21 @@ __global__ __launch_bounds__(C::kThreads) void linear_prefill_kernel(PatchSched<
     persistent_tiles<C>(sched, smem);
 }
 
+// Two tile configurations in one launch: every workgroup works through its share of the first schedule's
+// tiles and then of the second's, so the second part starts on each CU as soon as that CU is done with the
+// first (two launches would wait for the slowest workgroup, and pay a launch and a cold start).
+template <class C1, class C2>
+__global__ __launch_bounds__(C1::kThreads) void linear_prefill_pair_kernel(PatchSched<C1> first, PatchSched<C2> second) {
+    static_assert(C1::kThreads == C2::kThreads, "one workgroup shape");
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // the larger of the two layouts
+    persistent_tiles<C1>(first, smem);
+    // every wave's reads of the ring and of its staged output were waited for; nothing of the first part is
+    // left in LDS that the second part's loads could overwrite too early once all waves are here
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    persistent_tiles<C2>(second, smem);
+}
+
 __global__ __launch_bounds__(DecodeCfg::kThreads) void linear_decode_kernel(const LinearArgs single, const stwq_linear_problem* problems,
                                                                             int count, long long n_tiles, const GroupOrder order) {
     typedef DecodeCfg C;
@@ -1429,6 +1444,37 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
     return launch_status("linear_prefill_kernel");
 }
 
+template <class C>
+static int fill_patch_sched(const stwq::LinearArgs& p, stwq::PatchSched<C>& sched) {
+    using namespace stwq;
+    sched.p = p;
+    sched.tiles_o = (p.N + C::kTileO - 1) / C::kTileO;
+    sched.tiles_m = static_cast<int>((static_cast<long long>(p.M) + C::kTileM - 1) / C::kTileM);
+    const long long n_tiles = static_cast<long long>(sched.tiles_o) * sched.tiles_m;
+    STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
+    sched.n_tiles = static_cast<int>(n_tiles);
+    return STWQ_OK;
+}
+
+// Rows of `first` in tiles of C1, rows of `second` in tiles of C2, one launch.
+template <class C1, class C2>
+static int launch_prefill_pair(const stwq::LinearArgs& first, const stwq::LinearArgs& second, int cus, hipStream_t s) {
+    using namespace stwq;
+    constexpr int kLds = tile_lds<C1>() > tile_lds<C2>() ? tile_lds<C1>() : tile_lds<C2>();
+    static const int attr = set_ring(linear_prefill_pair_kernel<C1, C2>, kLds);
+    if (attr != STWQ_OK) return attr;
+    PatchSched<C1> a;
+    PatchSched<C2> b;
+    int rc = fill_patch_sched<C1>(first, a);
+    if (rc != STWQ_OK) return rc;
+    rc = fill_patch_sched<C2>(second, b);
+    if (rc != STWQ_OK) return rc;
+    const int most = a.n_tiles > b.n_tiles ? a.n_tiles : b.n_tiles;
+    const int grid = most < cus ? most : cus;
+    linear_prefill_pair_kernel<C1, C2><<<dim3(static_cast<unsigned>(grid)), dim3(C1::kThreads), kLds, s>>>(a, b);
+    return launch_status("linear_prefill_pair_kernel");
+}
+
 // Tile lists for a grouped streaming launch.  The cost of a tile is its K stages plus the epilogue and tile
 // switch, measured at 3.4 stages' worth (the output tile is a quarter of the bytes of an 11-stage tile's
 // weights).  Tiles in processing order (cost non-increasing) each go to the workgroup with the least work
@@ -1560,10 +1606,10 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
         bool narrow_tile = schedule == STWQ_SCHEDULE_PREFILL_NARROW;
         if (schedule == STWQ_SCHEDULE_PREFILL) {
             // Rounds of one tile per CU, in units of a wide tile's time; a narrow tile costs a little over half a
-            // wide one (measured: 0.57).  Three ways: all wide, all narrow, or the full rounds of wide tiles followed
-            // by a second launch that covers the remaining rows with narrow tiles (a last round of wide tiles that
-            // fills a third of the CUs costs a whole tile time; the same rows in narrow tiles cost 0.57).
-            constexpr double kNarrow = 0.57, kSecondLaunch = 0.08;
+            // wide one (measured: 0.57).  Three ways: all wide, all narrow, or the full rounds of wide tiles followed,
+            // in the same launch, by narrow tiles over the remaining rows (a last round of wide tiles that fills a
+            // third of the CUs costs a whole tile time; the same rows in narrow tiles cost 0.57).
+            constexpr double kNarrow = 0.57, kSecondLaunch = 0.02;
             const long long wide = prefill_tiles<PrefillCfg>(p), narrow = prefill_tiles<PrefillNarrowCfg>(p);
             const double t_wide = static_cast<double>((wide + cus - 1) / cus);
             const double t_narrow = kNarrow * static_cast<double>((narrow + cus - 1) / cus);
@@ -1583,8 +1629,7 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
                 if (t_split < t_wide && t_split < t_narrow) {
                     LinearArgs main = p;
                     main.M = static_cast<int>(m1);
-                    const int rc1 = launch_prefill<PrefillCfg>(main, cus, s);
-                    return rc1 != STWQ_OK ? rc1 : launch_prefill<PrefillNarrowCfg>(rest, cus, s);
+                    return launch_prefill_pair<PrefillCfg, PrefillNarrowCfg>(main, rest, cus, s);
                 }
             }
             narrow_tile = t_narrow < t_wide;
