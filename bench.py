@@ -329,9 +329,9 @@ def main() -> int:
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": achieved / INT8_MFMA_PEAK_TOPS,
                      "traffic": recorded_traffic("prefill_linear_traffic_bytes_per_launch"),
-                     "kernel": "stwq::linear_prefill_kernel", "avg_launch_us": lin_total_avg * 1e6,
-                     "note": "per call of stwq_linear; a call may dispatch the kernel twice (wide tiles for the full rounds, "
-                             "narrow tiles for the remaining rows)"},
+                     "kernel": "stwq::linear_prefill_kernel and stwq::linear_prefill_pair_kernel (the same tile loop; the pair "
+                               "kernel runs the full rounds in wide tiles and the remaining rows in narrow tiles)",
+                     "avg_launch_us": lin_total_avg * 1e6},
         "extra": extra,
     }
     if not args.skip_cpu_baseline:
