@@ -75,8 +75,10 @@ def calibrate_block(specs, device):
     return layers
 
 
-def time_launches(fn, n_warm, n_iter):
-    """Median and mean duration (seconds) of fn() measured with events on the current stream."""
+def time_launches(fn, n_warm, n_iter, batch=1):
+    """Median and mean duration (seconds) of fn() measured with events on the current stream.  With batch > 1 each
+    event pair brackets `batch` back-to-back calls and the time is per call: for kernels of a few microseconds, whose
+    single launches would be timed with the event's own cost and the host's launch path on top."""
     import torch
     for _ in range(n_warm):
         fn()
@@ -84,10 +86,11 @@ def time_launches(fn, n_warm, n_iter):
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_iter)]
     for a, b in evs:
         a.record()
-        fn()
+        for _ in range(batch):
+            fn()
         b.record()
     torch.cuda.synchronize()
-    ts = sorted(a.elapsed_time(b) * 1e-3 for a, b in evs)
+    ts = sorted(a.elapsed_time(b) * 1e-3 / batch for a, b in evs)
     return ts[len(ts) // 2], sum(ts) / len(ts)
 
 
@@ -285,19 +288,19 @@ def main() -> int:
     lay = layers[2]
     pm = torch.full((spec.L,), float("inf"), device=device)
     px = torch.full((spec.L,), float("-inf"), device=device)
-    med, _ = time_launches(lambda: B.stwq_calibrate_stats(xc, spec.L, inv_s=lay.inv_s, pos_min=pm, pos_max=px), 3, 20)
+    med, _ = time_launches(lambda: B.stwq_calibrate_stats(xc, spec.L, inv_s=lay.inv_s, pos_min=pm, pos_max=px), 3, 10, batch=8)
     extra["stats_position"] = {"us": med * 1e6, "gbs": 4.0 * xc.numel() / med / 1e9,
                                "frac_hbm_peak": 4.0 * xc.numel() / med / 1e9 / HBM_PEAK_GBS}
     cm = torch.full((spec.K,), float("inf"), device=device)
     cx = torch.full((spec.K,), float("-inf"), device=device)
     ca = torch.zeros(spec.K, device=device)
-    med, _ = time_launches(lambda: B.stwq_calibrate_stats(xc, spec.L, ch_min=cm, ch_max=cx, ch_absmax=ca), 3, 20)
+    med, _ = time_launches(lambda: B.stwq_calibrate_stats(xc, spec.L, ch_min=cm, ch_max=cx, ch_absmax=ca), 3, 10, batch=8)
     extra["stats_channel"] = {"us": med * 1e6, "gbs": 4.0 * xc.numel() / med / 1e9,
                               "frac_hbm_peak": 4.0 * xc.numel() / med / 1e9 / HBM_PEAK_GBS}
     wd = torch.from_numpy(wl.make_weights(spec)[0]).to(device)
     sd = lay.s
     tmp = StwqScratch(spec, device)
-    med, _ = time_launches(lambda: B.gps_fold_weights(wd, sd, 8, tmp.wq, tmp.dw, tmp.wsum, tmp.inv_s), 3, 20)
+    med, _ = time_launches(lambda: B.gps_fold_weights(wd, sd, 8, tmp.wq, tmp.dw, tmp.wsum, tmp.inv_s), 3, 10, batch=8)
     extra["fold"] = {"us": med * 1e6, "gbs": 5.0 * wd.numel() / med / 1e9,
                      "frac_hbm_peak": 5.0 * wd.numel() / med / 1e9 / HBM_PEAK_GBS}
     del xc, wd, tmp
