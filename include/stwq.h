@@ -151,9 +151,11 @@ STWQ_API int stwq_linear(const int8_t* q_dev, int64_t M, int K, int N, int L,
  * results; the integer part is bit-identical across schedules):
  *   STWQ_SCHEDULE_AUTO     what stwq_linear does;
  *   STWQ_SCHEDULE_GENERIC  one wave per 32 x 32 tile straight from global memory, any valid shape;
- *   STWQ_SCHEDULE_PREFILL  LDS-staged MFMA tiles (MFMA-bound shapes), K a multiple of 64; 256 x 256 or
- *                          128 x 256 (channels x rows), whichever needs less time in rounds of one tile per CU;
- *   STWQ_SCHEDULE_PREFILL_WIDE, STWQ_SCHEDULE_PREFILL_NARROW  the same with the tile named;
+ *   STWQ_SCHEDULE_PREFILL  LDS-staged MFMA tiles (MFMA-bound shapes), K a multiple of 64; tiles of 256 x 256
+ *                          or 128 x 256 (channels x rows), or 256 x 256 for as many rows as fill whole rounds
+ *                          of one tile per CU and 128 x 256 for the rest (in the same launch), whichever
+ *                          needs the least time;
+ *   STWQ_SCHEDULE_PREFILL_WIDE, STWQ_SCHEDULE_PREFILL_NARROW  one tile shape throughout, named;
  *   STWQ_SCHEDULE_DECODE   128 x 128 tiles (weight-streaming shapes, small M), K a multiple of 64;
  *   STWQ_SCHEDULE_STREAM   256 channels x 128 rows per workgroup, weights streamed from global memory straight
  *                          into registers and only the activations staged in LDS (weight-streaming shapes,

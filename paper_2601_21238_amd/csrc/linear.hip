@@ -1609,7 +1609,7 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
             // wide one (measured: 0.57).  Three ways: all wide, all narrow, or the full rounds of wide tiles followed,
             // in the same launch, by narrow tiles over the remaining rows (a last round of wide tiles that fills a
             // third of the CUs costs a whole tile time; the same rows in narrow tiles cost 0.57).
-            constexpr double kNarrow = 0.57, kSecondLaunch = 0.02;
+            constexpr double kNarrow = 0.57, kPartSwitch = 0.02;
             const long long wide = prefill_tiles<PrefillCfg>(p), narrow = prefill_tiles<PrefillNarrowCfg>(p);
             const double t_wide = static_cast<double>((wide + cus - 1) / cus);
             const double t_narrow = kNarrow * static_cast<double>((narrow + cus - 1) / cus);
@@ -1625,7 +1625,7 @@ static int launch_linear(const stwq::LinearArgs& p, int schedule, hipStream_t s)
                 rest.M = static_cast<int>(M - m1);
                 rest.t0 = static_cast<int>((p.t0 + m1) % p.L);
                 const double t_split = static_cast<double>((rows_main * tiles_o + cus - 1) / cus) +
-                                       kNarrow * static_cast<double>((prefill_tiles<PrefillNarrowCfg>(rest) + cus - 1) / cus) + kSecondLaunch;
+                                       kNarrow * static_cast<double>((prefill_tiles<PrefillNarrowCfg>(rest) + cus - 1) / cus) + kPartSwitch;
                 if (t_split < t_wide && t_split < t_narrow) {
                     LinearArgs main = p;
                     main.M = static_cast<int>(m1);
