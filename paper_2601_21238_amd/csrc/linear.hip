@@ -149,8 +149,9 @@ constexpr int kBK = 64;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
-template <int WO_, int WM_, int TI_, int TJ_, int STAGES_, int WAVE_STAGE_ = 8192>
+template <int WO_, int WM_, int TI_, int TJ_, int STAGES_, int WAVE_STAGE_ = 8192, int WGS_ = 1>
 struct TileCfg {
+    static constexpr int kWgsPerCu = WGS_;                // workgroups meant to share a CU (bounds the registers per wave)
     static constexpr int WO = WO_, WM = WM_, TI = TI_, TJ = TJ_, STAGES = STAGES_;
     static constexpr int kWaves = WO * WM;
     static constexpr int kThreads = kWaves * 64;
@@ -169,7 +170,8 @@ struct TileCfg {
     static constexpr int kJPerPass = kWaveStage / (32 * TI * 64);   // 32-token MFMA tiles staged per pass
     static_assert(kTileO % (16 * kWaves) == 0 && kTileM % (16 * kWaves) == 0, "tile rows must split over the waves");
     static_assert(kJPerPass >= 1 && TJ % kJPerPass == 0, "staging passes must divide the token tiles");
-    static_assert(STAGES >= 4, "two slots stage the output while the others keep streaming");
+    static constexpr int kStagingSlots = (kWaves * kWaveStage + kStage - 1) / kStage;   // ring slots the output is staged through
+    static_assert(STAGES >= kStagingSlots + 2, "the staging slots are idle while two others keep streaming");
     static_assert(kLoads * (STAGES - 1) <= 63, "vmcnt is a 6-bit counter");
 };
 typedef TileCfg<2, 4, 4, 2, 4> PrefillCfg;
@@ -536,7 +538,7 @@ __device__ __forceinline__ void epilogue(const LinearArgs& p, long long m0, int 
 // its epilogue leaves the load path idle.
 template <class C, class Sched>
 __device__ __forceinline__ void persistent_tiles(Sched& sched, int8_t* smem) {
-    constexpr int TI = C::TI, TJ = C::TJ, S = C::STAGES, E = 2;
+    constexpr int TI = C::TI, TJ = C::TJ, S = C::STAGES, E = C::kStagingSlots;
     static_assert(C::kWaves * C::kWaveStage <= E * C::kStage && C::kStage % C::kWaveStage == 0,
                   "output staging must fit two ring slots");
     static_assert(S - E >= 2, "stages 0 and 1 of a tile are requested ahead of the previous tile's epilogue");
@@ -758,7 +760,7 @@ struct DecodeSched {
 };
 
 template <class C>
-__global__ __launch_bounds__(C::kThreads) void linear_prefill_kernel(PatchSched<C> sched) {
+__global__ __launch_bounds__(C::kThreads, C::kWgsPerCu) void linear_prefill_kernel(PatchSched<C> sched) {
     extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // the ring, then two copies of the tile tables
     persistent_tiles<C>(sched, smem);
 }
@@ -1439,7 +1441,9 @@ static int launch_prefill(const stwq::LinearArgs& p, int cus, hipStream_t s) {
     const long long n_tiles = static_cast<long long>(sched.tiles_o) * sched.tiles_m;
     STWQ_REQUIRE(n_tiles <= 0x7FFFFFFFLL, "stwq_linear: too many tiles");
     sched.n_tiles = static_cast<int>(n_tiles);
-    const long long grid = n_tiles < cus ? n_tiles : cus;
+    static_assert(C::kWgsPerCu * tile_lds<C>() <= 160 * 1024, "LDS of one CU");
+    const long long slots = static_cast<long long>(cus) * C::kWgsPerCu;
+    const long long grid = n_tiles < slots ? n_tiles : slots;
     linear_prefill_kernel<C><<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), tile_lds<C>(), s>>>(sched);
     return launch_status("linear_prefill_kernel");
 }
