@@ -81,3 +81,43 @@ def test_config5_fc2_full():
     """3B-class fc2 (12288 -> 3072: the longest K of any configuration), M = 16384, W8A8, 4 calibration samples."""
     spec = wl.shrink(wl.config_linears(5)[3], n_calib=4)
     run_full(spec)
+
+
+@pytest.mark.timeout(600)
+def test_config4_decode_step_full():
+    """The whole RAR-XXL-shaped decode step bench.py times: 24 blocks x (qkv, fc1, fc2), M = 128 rows at one token
+    position per linear, one grouped quantization launch and one grouped linear launch on panel-packed weights
+    (960 tiles on 256 compute units: the launch runs from the balanced per-workgroup tile lists).  Every offline
+    quantity, activation code, accumulator and output of all 72 linears is compared with the oracle."""
+    specs = wl.config_linears(4)
+    assert len(specs) == 72
+    qproblems, problems, refs, keep = [], [], [], []
+    for spec in specs:
+        w, b, xc, xt = G.make_case(spec)
+        t0 = wl.decode_position(spec)
+        pack = G.oracle_pack(spec, xc, w, b)
+        layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+        G.check_calibration(layer, pack)
+        q_ref, acc_ref, y_ref = O.forward(pack, xt, t0=t0)
+        packed = torch.empty(P.stwq_packed_weight_bytes(spec.N, spec.K), dtype=torch.int8, device=G.DEV)
+        P.stwq_pack_weights(layer.wq, packed)
+        q = torch.zeros((spec.M, spec.K), dtype=torch.int8, device=G.DEV)
+        qproblems.append(dict(x=G.dev(xt), L=1, inv_s=layer.inv_s, inv_delta=layer.inv_delta[t0:t0 + 1], zp=layer.zp[t0:t0 + 1],
+                              a_bits=spec.a_bits, q=q))
+        problems.append(dict(q=q, wq=packed, N=spec.N, w_layout=P.LAYOUT_PANEL32, dw=layer.dw, wsum=layer.wsum,
+                             delta=layer.delta[t0:t0 + 1], zp=layer.zp[t0:t0 + 1], a_bits=spec.a_bits, bias=layer.bias, L=1,
+                             y=torch.zeros((spec.M, spec.N), dtype=torch.bfloat16, device=G.DEV),
+                             acc_dbg=torch.zeros((spec.M, spec.N), dtype=torch.int32, device=G.DEV)))
+        refs.append((q_ref, acc_ref, y_ref, pack["bias"]))
+        keep.append(layer)
+        del w, xc
+    _, lists = P.stwq_linear_grouped_plan([(s.M, s.K, s.N) for s in specs], 256)
+    assert lists is not None and sum(len(l) for l in lists) == 960
+    P.QuantizeGroup(qproblems).run()
+    P.LinearGroup(problems).run()
+    torch.cuda.synchronize()
+    for spec, qp, pr, (q_ref, acc_ref, y_ref, bias) in zip(specs, qproblems, problems, refs):
+        what = f"config 4, block {spec.layer}, {spec.name}"
+        assert np.array_equal(G.host(qp["q"]), q_ref), f"{what}: activation codes differ"
+        assert np.array_equal(G.host(pr["acc_dbg"]), acc_ref), f"{what}: accumulators differ"
+        G.check_bf16(pr["y"], y_ref, what, bias)
