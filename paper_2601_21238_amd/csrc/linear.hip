@@ -1480,7 +1480,7 @@ static int launch_prefill_pair(const stwq::LinearArgs& first, const stwq::Linear
 }
 
 // Tile lists for a grouped streaming launch.  The cost of a tile is its K stages plus the epilogue and tile
-// switch, measured at 3.4 stages' worth (the output tile is a quarter of the bytes of an 11-stage tile's
+// switch, measured at 3.4 stages' worth (the output tile is a fifth of the bytes of a 10-stage tile's
 // weights).  Tiles in processing order (cost non-increasing) each go to the workgroup with the least work
 // so far, among the workgroups `owner` allows for the tile's problem.
 struct StreamLists {

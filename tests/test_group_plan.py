@@ -28,7 +28,7 @@ def tile_table(shapes, order):
 def decode_step_shapes(layers):
     shapes = []
     for _ in range(layers):
-        shapes += [(128, 1408, 4224), (128, 1408, 5632), (128, 5632, 1408)]
+        shapes += [(128, 1280, 3840), (128, 1280, 5120), (128, 5120, 1280)]      # configuration 4: qkv, fc1, fc2
     return shapes
 
 
@@ -80,7 +80,7 @@ def test_plan_is_cached_and_redone_when_shapes_change():
     o2, l2 = P.stwq_linear_grouped_plan(a, 64)
     assert l1 == l2 and np.array_equal(o1, o2)
     b = list(a)
-    b[4] = (128, 2816, 1408)
+    b[4] = (128, 2560, 1280)
     o3, l3 = P.stwq_linear_grouped_plan(b, 64)
     check_lists(b, o3, l3, 64)
     o4, l4 = P.stwq_linear_grouped_plan(a, 128)               # another grid: other lists
@@ -88,10 +88,10 @@ def test_plan_is_cached_and_redone_when_shapes_change():
 
 
 def test_no_lists_when_they_are_not_needed_or_do_not_fit():
-    assert P.stwq_linear_grouped_plan([(128, 1408, 4224)], 256)[1] is None           # 17 tiles, 256 workgroups
-    many = [(128, 1408, 5632)] * 100                                                   # 2200 tiles: too many for the arguments
+    assert P.stwq_linear_grouped_plan([(128, 1280, 3840)], 256)[1] is None           # 15 tiles, 256 workgroups
+    many = [(128, 1280, 5120)] * 100                                                   # 2000 tiles: too many for the arguments
     assert P.stwq_linear_grouped_plan(many, 256)[1] is None
     with pytest.raises(P.StwqError):
         P.stwq_linear_grouped_plan([(0, 64, 64)], 256)
     with pytest.raises(P.StwqError):
-        P.stwq_linear_grouped_plan([(128, 1408, 4224)], 0)
+        P.stwq_linear_grouped_plan([(128, 1280, 3840)], 0)
