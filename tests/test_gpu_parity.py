@@ -356,3 +356,20 @@ def test_grouped_balanced_lists():
     torch.cuda.synchronize()
     for pr, y in zip(problems, first):
         assert torch.equal(pr["y"], y)
+
+
+def test_wide_and_narrow_tiles_in_one_launch():
+    """A shape whose 256 x 256 tiles fill one round of the 256 compute units and a little more (258 of them): the
+    auto schedule runs the full round in wide tiles and the remaining rows in narrow tiles, in one launch.  The
+    second part starts at a row that is not a multiple of L, so its rows index the per-position tables from an
+    offset.  Every code, accumulator and output is compared; the named single-tile schedules give the same bits."""
+    spec = small_spec(K=64, N=256, L=37, batch=1781, n_calib=2, a_bits=8, w_bits=8, n_outliers=4)
+    assert spec.M == 65897
+    w, b, xc, xt = G.make_case(spec)
+    pack = G.oracle_pack(spec, xc, w, b)
+    layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+    G.check_calibration(layer, pack)
+    q, acc, y = G.check_forward(layer, pack, xt, P.SCHEDULE_PREFILL, what="wide + narrow")
+    for sch in ("wide", "narrow"):
+        y2 = layer.linear(q, schedule=SCHEDULES[sch])
+        assert torch.equal(y2, y), sch
