@@ -11,6 +11,7 @@
 // Inside one MFMA both operands take the same 16-byte K chunk per lane, and integer sums commute,
 // so any consistent assignment of K chunks to lanes gives the exact result.
 #include <algorithm>
+#include <cstddef>
 #include <functional>
 #include <queue>
 #include <utility>
@@ -1099,6 +1100,37 @@ __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m
     }
 }
 
+// The arguments of a problem from a copy of its descriptor in LDS (asm reads: a load the compiler could see
+// would make it wait for every direct-to-LDS load in flight).  Field offsets are those of stwq_linear_problem.
+__device__ __forceinline__ uint64_t uniform_u64(int lo, int hi) {
+    return (static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(hi))) << 32) |
+           static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(lo));
+}
+__device__ __forceinline__ LinearArgs args_of_lds(unsigned addr, int& layout) {
+    static_assert(sizeof(stwq_linear_problem) == 96 && offsetof(stwq_linear_problem, M) == 72 &&
+                  offsetof(stwq_linear_problem, w_layout) == 92, "descriptor layout");
+    v4i d0 = lds_ld16<0>(addr), d1 = lds_ld16<16>(addr), d2 = lds_ld16<32>(addr), d3 = lds_ld16<48>(addr),
+        d4 = lds_ld16<64>(addr), d5 = lds_ld16<80>(addr);
+    wait_lgkm<0>();
+    settle(d0); settle(d1); settle(d2); settle(d3); settle(d4); settle(d5);
+    LinearArgs p;
+    p.q = reinterpret_cast<const int8_t*>(uniform_u64(d0[0], d0[1]));
+    p.wq = reinterpret_cast<const int8_t*>(uniform_u64(d0[2], d0[3]));
+    p.dw = reinterpret_cast<const float*>(uniform_u64(d1[0], d1[1]));
+    p.wsum = reinterpret_cast<const int32_t*>(uniform_u64(d1[2], d1[3]));
+    p.delta = reinterpret_cast<const float*>(uniform_u64(d2[0], d2[1]));
+    p.zp = reinterpret_cast<const int32_t*>(uniform_u64(d2[2], d2[3]));
+    p.bias = reinterpret_cast<const float*>(uniform_u64(d3[0], d3[1]));
+    p.y = reinterpret_cast<uint16_t*>(uniform_u64(d3[2], d3[3]));
+    p.acc_dbg = reinterpret_cast<int32_t*>(uniform_u64(d4[0], d4[1]));
+    p.M = __builtin_amdgcn_readfirstlane(d4[2]); p.K = __builtin_amdgcn_readfirstlane(d4[3]);
+    p.N = __builtin_amdgcn_readfirstlane(d5[0]); p.L = __builtin_amdgcn_readfirstlane(d5[1]);
+    p.off = __builtin_amdgcn_readfirstlane(d5[2]) == 8 ? 128 : 0;
+    p.t0 = 0;
+    layout = __builtin_amdgcn_readfirstlane(d5[3]);
+    return p;
+}
+
 // Decode schedule for the streaming kernel.  Tiles are numbered along the concatenated tile lists of the
 // problems in processing order (longest K first; channel tiles fastest within a problem).  A workgroup
 // either takes every gridDim.x-th tile, or, when the host has balanced the launch, the tiles of its own
@@ -1106,17 +1138,20 @@ __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m
 // handful, so dealing them out in turn leaves some workgroups with a third more work than the average.
 constexpr int kPlanEntries = 1792;
 struct GroupPlan {
-    // [0, count): problem index at each position of the processing order; when planned, then gridDim.x + 1
-    // list starts and after them the tile ids of all lists, one list per workgroup
+    // [0, count): problem index at each position of the processing order; when planned, then count + 1 running
+    // tile counts in that order (from 0), gridDim.x + 1 list starts, and the tile ids of all lists, one list per
+    // workgroup
     uint16_t v[kPlanEntries];
 };
+constexpr int kDescCache = 128;          // descriptors of groups up to this size are kept in LDS
 template <class C>
 struct StreamSched {
     LinearArgs single;
     const stwq_linear_problem* problems;
     unsigned prefix;           // LDS address of count + 1 running tile counts, problems in processing order
     unsigned order;            // LDS address of the problem index (16 bits) at each position of that order
-    unsigned list;             // LDS address of the tile ids (16 bits) of all lists, or 0: every gridDim.x-th tile
+    unsigned list;             // LDS address of this workgroup's tile ids (16 bits), or 0: every gridDim.x-th tile
+    unsigned desc;             // LDS address of a copy of all descriptors, or 0: read them from global memory
     int pos, end;              // this workgroup's range in `list`
     long long v, n_tiles;      // next tile id when there are no lists
     int cursor;                // position in the order of the previous tile (tiles are visited in increasing order)
@@ -1137,9 +1172,14 @@ struct StreamSched {
             while (tile >= __builtin_amdgcn_readfirstlane(lds_ld4_now(prefix + 4 * (i + 1)))) ++i;   // scalar condition: a uniform loop
             cursor = i;
             tile -= __builtin_amdgcn_readfirstlane(lds_ld4_now(prefix + 4 * i));
-            const stwq_linear_problem& q = problems[__builtin_amdgcn_readfirstlane(lds_ld2_now(order + 2 * i))];
-            t.p = args_of(q);
-            layout = __builtin_amdgcn_readfirstlane(q.w_layout);
+            const int idx = __builtin_amdgcn_readfirstlane(lds_ld2_now(order + 2 * i));
+            if (desc) {        // no round trip to memory between two tiles
+                t.p = args_of_lds(desc + idx * static_cast<unsigned>(sizeof(stwq_linear_problem)), layout);
+            } else {
+                const stwq_linear_problem& q = problems[idx];
+                t.p = args_of(q);
+                layout = __builtin_amdgcn_readfirstlane(q.w_layout);
+            }
         } else {
             t.p = single;
         }
@@ -1294,39 +1334,69 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
     wait_lgkm<0>();                               // the last B prefetch read a slot nobody consumes; drain it
 }
 
+// Dynamic LDS of the streaming kernel after the ring, the output staging and the two tile tables: running tile
+// counts, the plan entries this workgroup needs, copies of the descriptors (read 16 bytes at a time).
+template <class C>
+struct StreamLds {
+    static constexpr int kOffPrefix = C::kOffTables + 2 * TileTables<C>::kBytes;
+    static constexpr int kOffPlan = kOffPrefix + (kMaxGroup + 1) * 4;
+    static constexpr int kOffDesc = (kOffPlan + kPlanEntries * 2 + 15) / 16 * 16;
+    static constexpr int kBytes = kOffDesc + kDescCache * static_cast<int>(sizeof(stwq_linear_problem));
+    static_assert(C::kOffTables % 16 == 0 && TileTables<C>::kBytes % 16 == 0, "the offsets above assume a 16-byte aligned start");
+};
+
 template <class C>
 __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu) void linear_stream_kernel(const LinearArgs single,
                                                                                 const stwq_linear_problem* __restrict__ problems,
                                                                                 int count, long long n_tiles, int planned,
                                                                                 const GroupPlan plan) {
-    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // ring, output staging, two tile tables, tile counts, plan
-    constexpr int kOffPrefix = C::kOffTables + 2 * TileTables<C>::kBytes, kOffPlan = kOffPrefix + (kMaxGroup + 1) * 4;
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];   // ring, output staging, two tile tables, tile counts, plan, descriptors
+    constexpr int kOffPrefix = StreamLds<C>::kOffPrefix, kOffPlan = StreamLds<C>::kOffPlan, kOffDesc = StreamLds<C>::kOffDesc;
     int* prefix = reinterpret_cast<int*>(smem + kOffPrefix);
     uint16_t* pl = reinterpret_cast<uint16_t*>(smem + kOffPlan);
     const int G = gridDim.x;
-    if (problems) {   // plain LDS accesses: no direct-to-LDS load has been issued yet
-        const int used = count + (planned ? G + 1 + static_cast<int>(n_tiles) : 0);
-        for (int i = threadIdx.x; i < used; i += C::kThreads) pl[i] = plan.v[i];
-        for (int i = threadIdx.x; i < count; i += C::kThreads) {
-            const stwq_linear_problem& q = problems[plan.v[i]];
-            prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
-        }
-        __syncthreads();
-        running_counts(prefix, count);
-        __syncthreads();
-    }
     StreamSched<C> sched;
+    sched.list = 0;
+    sched.desc = 0;
+    sched.pos = sched.end = 0;
+    if (problems) {   // plain LDS accesses: no direct-to-LDS load has been issued yet
+        // Everything below is one round of independent loads and one barrier: the launch is a hundred microseconds
+        // long, and a chain of dependent loads here (list -> descriptor -> tile count) cost several of them.
+        if (count <= kDescCache) {
+            const global_v4i* src = (const global_v4i*)problems;
+            v4i* dst = reinterpret_cast<v4i*>(smem + kOffDesc);
+            const int n16 = count * static_cast<int>(sizeof(stwq_linear_problem) / 16);
+            for (int e = threadIdx.x; e < n16; e += C::kThreads) dst[e] = src[e];
+            sched.desc = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst));
+        }
+        if (planned) {   // the host has summed the tile counts; only this workgroup's list is copied
+            const uint16_t* counts = plan.v + count, *starts = counts + count + 1, *tiles = starts + G + 1;
+            for (int i = threadIdx.x; i < count; i += C::kThreads) {
+                pl[i] = plan.v[i];
+                prefix[i + 1] = counts[i + 1];
+            }
+            if (threadIdx.x == 0) prefix[0] = 0;
+            const int first = starts[blockIdx.x], n = starts[blockIdx.x + 1] - first;
+            uint16_t* mine = pl + count;
+            for (int i = threadIdx.x; i < n; i += C::kThreads) mine[i] = tiles[first + i];
+            sched.list = static_cast<unsigned>(reinterpret_cast<uintptr_t>(mine));
+            sched.end = n;
+            __syncthreads();
+        } else {
+            for (int i = threadIdx.x; i < count; i += C::kThreads) {
+                const stwq_linear_problem& q = problems[plan.v[i]];
+                pl[i] = plan.v[i];
+                prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+            }
+            __syncthreads();
+            running_counts(prefix, count);
+            __syncthreads();
+        }
+    }
     sched.single = single;
     sched.problems = problems;
     sched.prefix = static_cast<unsigned>(reinterpret_cast<uintptr_t>(prefix));
     sched.order = static_cast<unsigned>(reinterpret_cast<uintptr_t>(pl));
-    sched.list = 0;
-    sched.pos = sched.end = 0;
-    if (problems && planned) {
-        sched.list = sched.order + 2 * (count + G + 1);
-        sched.pos = pl[count + blockIdx.x];
-        sched.end = pl[count + blockIdx.x + 1];
-    }
     // Without lists: stride gridDim.x from a permutation of the block id that gives the 8 XCDs (which take
     // workgroup ids in turn) contiguous runs of tiles.
     sched.v = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
@@ -1523,7 +1593,7 @@ static StreamLists deal_stream_tiles(const stwq_linear_problem* problems, const 
 template <class C>
 static bool plan_stream_lists(const stwq_linear_problem* problems, int count, long long n_tiles, int grid, stwq::GroupPlan& plan) {
     using namespace stwq;
-    if (grid > 0xFFFF || count + grid + 1 + n_tiles > kPlanEntries) return false;
+    if (grid > 0xFFFF || 2 * count + 1 + grid + 1 + n_tiles > kPlanEntries) return false;
     // the last plan, kept per thread: a decode loop launches the same group of shapes every step
     struct Key { int M, K, N; };
     thread_local std::vector<Key> last_key;
@@ -1557,7 +1627,13 @@ static bool plan_stream_lists(const stwq_linear_problem* problems, int count, lo
         StreamLists local = deal_stream_tiles<C>(problems, plan.v, count, grid, kXcds, owner);
         if (local.longest * 100 <= lists.longest * 103) lists = std::move(local);
     }
-    uint16_t* start = plan.v + count;
+    uint16_t* counts = plan.v + count;              // running tile counts in processing order, from 0
+    counts[0] = 0;
+    for (int i = 0; i < count; ++i) {
+        const stwq_linear_problem& q = problems[plan.v[i]];
+        counts[i + 1] = static_cast<uint16_t>(counts[i] + ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO));
+    }
+    uint16_t* start = counts + count + 1;
     uint16_t* out = start + grid + 1;
     int n = 0;
     for (int g = 0; g < grid; ++g) {
@@ -1577,7 +1653,7 @@ template <class C>
 static int launch_stream(const stwq::LinearArgs& single, const stwq_linear_problem* problems, const stwq_linear_problem* problems_dev,
                          int count, long long n_tiles, stwq::GroupPlan& plan, hipStream_t s) {
     using namespace stwq;
-    constexpr int kLds = C::kOffTables + 2 * TileTables<C>::kBytes + (kMaxGroup + 1) * 4 + kPlanEntries * 2;
+    constexpr int kLds = StreamLds<C>::kBytes;
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     static_assert(C::kWgsPerCu * kLds <= 160 * 1024, "LDS of one CU");
     static const int attr = set_ring(linear_stream_kernel<C>, kLds);
@@ -1735,8 +1811,9 @@ extern "C" int stwq_linear_grouped_plan(const stwq_linear_problem* problems, int
     const long long grid = n_tiles < workgroups ? n_tiles : workgroups;
     if (n_tiles <= grid || !plan_stream_lists<C>(problems, count, n_tiles, static_cast<int>(grid), plan)) return 0;
     STWQ_REQUIRE(n_tiles <= tiles_capacity, "stwq_linear_grouped_plan: %lld tiles, room for %d", n_tiles, tiles_capacity);
-    std::copy(plan.v + count, plan.v + count + grid + 1, starts_out);
-    std::copy(plan.v + count + grid + 1, plan.v + count + grid + 1 + n_tiles, tiles_out);
+    const uint16_t* starts = plan.v + 2 * count + 1;
+    std::copy(starts, starts + grid + 1, starts_out);
+    std::copy(starts + grid + 1, starts + grid + 1 + n_tiles, tiles_out);
     return static_cast<int>(n_tiles);
 }
 
