@@ -1139,8 +1139,8 @@ __device__ __forceinline__ LinearArgs args_of_lds(unsigned addr, int& layout) {
 constexpr int kPlanEntries = 1792;
 struct GroupPlan {
     // [0, count): problem index at each position of the processing order; when planned, then count + 1 running
-    // tile counts in that order (from 0), gridDim.x + 1 list starts, and the tile ids of all lists, one list per
-    // workgroup
+    // tile counts in that order (from 0) and one list per workgroup at a fixed stride: its length, then its tile
+    // ids (a fixed stride, so that a workgroup fetches its list without first fetching where it starts)
     uint16_t v[kPlanEntries];
 };
 constexpr int kDescCache = 128;          // descriptors of groups up to this size are kept in LDS
@@ -1361,32 +1361,63 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu) void linear_stream_kerne
     sched.pos = sched.end = 0;
     if (problems) {   // plain LDS accesses: no direct-to-LDS load has been issued yet
         // Everything below is one round of independent loads and one barrier: the launch is a hundred microseconds
-        // long, and a chain of dependent loads here (list -> descriptor -> tile count) cost several of them.
-        if (count <= kDescCache) {
-            const global_v4i* src = (const global_v4i*)problems;
-            v4i* dst = reinterpret_cast<v4i*>(smem + kOffDesc);
-            const int n16 = count * static_cast<int>(sizeof(stwq_linear_problem) / 16);
-            for (int e = threadIdx.x; e < n16; e += C::kThreads) dst[e] = src[e];
-            sched.desc = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst));
+        // long, and a chain of dependent loads here (list -> descriptor -> tile count) cost several of them.  All
+        // loads of the round are issued before the first of their values is stored.
+        constexpr int kDescLoads = kDescCache * static_cast<int>(sizeof(stwq_linear_problem) / 16) / C::kThreads;
+        static_assert(kDescLoads * C::kThreads == kDescCache * static_cast<int>(sizeof(stwq_linear_problem) / 16), "whole rounds");
+        const bool cached = count <= kDescCache;
+        const int n16 = cached ? count * static_cast<int>(sizeof(stwq_linear_problem) / 16) : 0;
+        v4i* desc_lds = reinterpret_cast<v4i*>(smem + kOffDesc);
+        v4i desc_part[kDescLoads];
+#pragma unroll
+        for (int u = 0; u < kDescLoads; ++u) {
+            const int e = threadIdx.x + u * C::kThreads;
+            if (e < n16) desc_part[u] = ((const global_v4i*)problems)[e];
         }
-        if (planned) {   // the host has summed the tile counts; only this workgroup's list is copied
-            const uint16_t* counts = plan.v + count, *starts = counts + count + 1, *tiles = starts + G + 1;
-            for (int i = threadIdx.x; i < count; i += C::kThreads) {
-                pl[i] = plan.v[i];
-                prefix[i + 1] = counts[i + 1];
+        if (cached) sched.desc = static_cast<unsigned>(reinterpret_cast<uintptr_t>(desc_lds));
+        if (planned) {   // the host has summed the tile counts; only this workgroup's list is copied (planned = its stride)
+            const uint16_t* counts = plan.v + count, *list = counts + count + 1 + blockIdx.x * planned;
+            constexpr int kPer = kMaxGroup / C::kThreads;
+            uint16_t ord_part[kPer], cnt_part[kPer], list_part = 0;
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int i = threadIdx.x + u * C::kThreads;
+                ord_part[u] = i < count ? plan.v[i] : 0;
+                cnt_part[u] = i < count ? counts[i + 1] : 0;
+            }
+            const bool short_list = planned <= C::kThreads;      // longer lists: the rest is copied in a loop below
+            if (threadIdx.x < planned) list_part = list[threadIdx.x];
+            uint16_t* mine = pl + count;
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int i = threadIdx.x + u * C::kThreads;
+                if (i < count) {
+                    pl[i] = ord_part[u];
+                    prefix[i + 1] = cnt_part[u];
+                }
             }
             if (threadIdx.x == 0) prefix[0] = 0;
-            const int first = starts[blockIdx.x], n = starts[blockIdx.x + 1] - first;
-            uint16_t* mine = pl + count;
-            for (int i = threadIdx.x; i < n; i += C::kThreads) mine[i] = tiles[first + i];
-            sched.list = static_cast<unsigned>(reinterpret_cast<uintptr_t>(mine));
-            sched.end = n;
+            if (threadIdx.x < planned) mine[threadIdx.x] = list_part;     // length, then tile ids
+            if (!short_list)
+                for (int i = threadIdx.x + C::kThreads; i < planned; i += C::kThreads) mine[i] = list[i];
+#pragma unroll
+            for (int u = 0; u < kDescLoads; ++u) {
+                const int e = threadIdx.x + u * C::kThreads;
+                if (e < n16) desc_lds[e] = desc_part[u];
+            }
             __syncthreads();
+            sched.list = static_cast<unsigned>(reinterpret_cast<uintptr_t>(mine + 1));
+            sched.end = mine[0];
         } else {
             for (int i = threadIdx.x; i < count; i += C::kThreads) {
                 const stwq_linear_problem& q = problems[plan.v[i]];
                 pl[i] = plan.v[i];
                 prefix[i + 1] = ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO);
+            }
+#pragma unroll
+            for (int u = 0; u < kDescLoads; ++u) {
+                const int e = threadIdx.x + u * C::kThreads;
+                if (e < n16) desc_lds[e] = desc_part[u];
             }
             __syncthreads();
             running_counts(prefix, count);
@@ -1591,19 +1622,22 @@ static StreamLists deal_stream_tiles(const stwq_linear_problem* problems, const 
 // may go to any workgroup.  (1) is taken unless it leaves the busiest workgroup with over 3 % more work
 // than (2).  Returns false when the lists do not fit the plan.
 template <class C>
-static bool plan_stream_lists(const stwq_linear_problem* problems, int count, long long n_tiles, int grid, stwq::GroupPlan& plan) {
+static bool plan_stream_lists(const stwq_linear_problem* problems, int count, long long n_tiles, int grid, stwq::GroupPlan& plan,
+                              int& stride) {
     using namespace stwq;
-    if (grid > 0xFFFF || 2 * count + 1 + grid + 1 + n_tiles > kPlanEntries) return false;
+    if (n_tiles > 0xFFFF || 2 * count + 1 + 2LL * grid > kPlanEntries) return false;
     // the last plan, kept per thread: a decode loop launches the same group of shapes every step
     struct Key { int M, K, N; };
     thread_local std::vector<Key> last_key;
     thread_local int last_grid = 0;
     thread_local GroupPlan last_plan;
+    thread_local int last_stride = 0;
     bool same = last_grid == grid && static_cast<int>(last_key.size()) == count;
     for (int i = 0; same && i < count; ++i)
         same = last_key[i].M == problems[i].M && last_key[i].K == problems[i].K && last_key[i].N == problems[i].N;
     if (same) {
         plan = last_plan;
+        stride = last_stride;
         return true;
     }
     StreamLists lists = deal_stream_tiles<C>(problems, plan.v, count, grid, 1, std::vector<int>(count, 0));
@@ -1633,14 +1667,16 @@ static bool plan_stream_lists(const stwq_linear_problem* problems, int count, lo
         const stwq_linear_problem& q = problems[plan.v[i]];
         counts[i + 1] = static_cast<uint16_t>(counts[i] + ((q.M + C::kTileM - 1) / C::kTileM) * ((q.N + C::kTileO - 1) / C::kTileO));
     }
-    uint16_t* start = counts + count + 1;
-    uint16_t* out = start + grid + 1;
-    int n = 0;
-    for (int g = 0; g < grid; ++g) {
-        start[g] = static_cast<uint16_t>(n);
-        for (uint16_t t : lists.tiles[g]) out[n++] = t;
+    size_t longest = 0;
+    for (int g = 0; g < grid; ++g) longest = std::max(longest, lists.tiles[g].size());
+    stride = static_cast<int>(longest) + 1;
+    if (2 * count + 1 + static_cast<long long>(grid) * stride > kPlanEntries) return false;
+    uint16_t* out = counts + count + 1;
+    for (int g = 0; g < grid; ++g, out += stride) {
+        out[0] = static_cast<uint16_t>(lists.tiles[g].size());
+        std::copy(lists.tiles[g].begin(), lists.tiles[g].end(), out + 1);
     }
-    start[grid] = static_cast<uint16_t>(n);
+    last_stride = stride;
     last_key.resize(count);
     for (int i = 0; i < count; ++i) last_key[i] = Key{problems[i].M, problems[i].K, problems[i].N};
     last_grid = grid;
@@ -1663,9 +1699,10 @@ static int launch_stream(const stwq::LinearArgs& single, const stwq_linear_probl
     if (rc != STWQ_OK) return rc;
     const long long slots = static_cast<long long>(cus) * C::kWgsPerCu;
     const long long grid = n_tiles < slots ? n_tiles : slots;
-    const bool planned = problems && n_tiles > grid && plan_stream_lists<C>(problems, count, n_tiles, static_cast<int>(grid), plan);
+    int stride = 0;       // entries per workgroup list in the plan; 0: tiles are dealt out in turn
+    if (!(problems && n_tiles > grid && plan_stream_lists<C>(problems, count, n_tiles, static_cast<int>(grid), plan, stride))) stride = 0;
     linear_stream_kernel<C><<<dim3(static_cast<unsigned>(grid)), dim3(C::kThreads), kLds, s>>>(single, problems_dev, count, n_tiles,
-                                                                                           planned ? 1 : 0, plan);
+                                                                                           stride, plan);
     return launch_status("linear_stream_kernel");
 }
 
@@ -1809,12 +1846,18 @@ extern "C" int stwq_linear_grouped_plan(const stwq_linear_problem* problems, int
     std::stable_sort(plan.v, plan.v + count, [&](uint16_t a, uint16_t b) { return problems[a].K > problems[b].K; });
     std::copy(plan.v, plan.v + count, order_out);
     const long long grid = n_tiles < workgroups ? n_tiles : workgroups;
-    if (n_tiles <= grid || !plan_stream_lists<C>(problems, count, n_tiles, static_cast<int>(grid), plan)) return 0;
+    int stride = 0;
+    if (n_tiles <= grid || !plan_stream_lists<C>(problems, count, n_tiles, static_cast<int>(grid), plan, stride)) return 0;
     STWQ_REQUIRE(n_tiles <= tiles_capacity, "stwq_linear_grouped_plan: %lld tiles, room for %d", n_tiles, tiles_capacity);
-    const uint16_t* starts = plan.v + 2 * count + 1;
-    std::copy(starts, starts + grid + 1, starts_out);
-    std::copy(starts + grid + 1, starts + grid + 1 + n_tiles, tiles_out);
-    return static_cast<int>(n_tiles);
+    const uint16_t* list = plan.v + 2 * count + 1;
+    int n = 0;
+    for (int g = 0; g < grid; ++g, list += stride) {
+        starts_out[g] = static_cast<uint16_t>(n);
+        std::copy(list + 1, list + 1 + list[0], tiles_out + n);
+        n += list[0];
+    }
+    starts_out[grid] = static_cast<uint16_t>(n);
+    return n;
 }
 
 extern "C" int stwq_pack_weights(const int8_t* wq_dev, int N, int K, int8_t* packed_dev, void* stream) {
