@@ -1040,9 +1040,16 @@ __device__ __forceinline__ void stream_consts(unsigned cbase, v4i (&dwv)[sizeof.
     ((dwv[CH] = lds_ld16<T::kDw + 32 * CH>(cbase)), ...);
     ((bv[CH] = lds_ld16<T::kBias + 32 * CH>(cbase)), ...);
 }
+template <class C, int... G>
+__device__ __forceinline__ void stream_row_sums(unsigned addr, v4i (&wsv)[sizeof...(G)], std::integer_sequence<int, G...>) {
+    ((wsv[G] = lds_ld16<32 * G>(addr)), ...);
+}
+// `next_tab` (0 if this is the workgroup's last tile): LDS address of the next tile's tables, which have landed.
+// The accumulators of row tile j are then started for the next tile (init_acc's arithmetic) right after pass j
+// has read them, while that pass's staged rows are on their way back from LDS.
 template <class C>
 __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m0, int o0, v16i (&acc)[C::TI][C::TJ], unsigned stage,
-                                                unsigned tab, int lane, int wave) {
+                                                unsigned tab, unsigned next_tab, int next_off, int lane, int wave) {
     typedef TileTables<C> T;
     asm volatile("" : "+v"(lane));   // lane-dependent addresses are recomputed per call, not kept in registers across the K loop
     constexpr int TI = C::TI, TJ = C::TJ, OC = C::kChunks;
@@ -1053,7 +1060,24 @@ __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m
     for (int j = 0; j < TJ; ++j) dtb[j] = lds_ld4<T::kDelta>(tab + (j * 32 + l32) * 4);
     v4i dwv[OC], bv[OC];
     stream_consts<C>(tab + (wave * TI * 32 + 4 * hi) * 4, dwv, bv, std::make_integer_sequence<int, OC>{});
+    // the next tile's row sums (chunk c = 4 i + g as above) and zero points
+    v4i wsv[OC];
+    int zs[TJ];
+    if (next_tab) {
+        stream_row_sums<C>(next_tab + T::kWs + (wave * TI * 32 + 4 * hi) * 4, wsv, std::make_integer_sequence<int, OC>{});
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) zs[j] = lds_ld4<T::kZp>(next_tab + (j * 32 + l32) * 4);
+    }
     wait_lgkm<0>();
+    if (next_tab) {
+#pragma unroll
+        for (int c = 0; c < OC; ++c) settle(wsv[c]);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            settle(zs[j]);
+            zs[j] = next_off - zs[j];        // minus the zero point of the stored codes
+        }
+    }
     float dt[TJ];
 #pragma unroll
     for (int j = 0; j < TJ; ++j) {
@@ -1086,6 +1110,12 @@ __device__ __forceinline__ void stream_epilogue(const LinearArgs& p, long long m
         for (int u = 0; u < kReads; ++u) {
             const int row = u * kRowsPerRead + rr;
             v[u] = lds_ld16(stage + row * kRowBytes + ((cc ^ (row & (OC - 1))) * 16));
+        }
+        if (next_tab) {
+#pragma unroll
+            for (int c = 0; c < OC; ++c)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[c >> 2][j][4 * (c & 3) + r] = __mul24(zs[j], wsv[c][r]);
         }
         wait_lgkm<0>();
         const long long mbase = m0 + j * 32 + rr;
@@ -1313,15 +1343,18 @@ __device__ __forceinline__ void stream_tiles(Sched& sched, int8_t* smem) {
                             }
                     }
                 }
-                if (C::kWgsPerCu == 1)
-                    stream_epilogue<C>(p, cur.m0, cur.o0, acc, lds_base + C::kOffStaging + wave * C::kWaveStage, tab, lane, wave);
-                else   // half the registers and a second wave on the SIMD to cover LDS round trips: constants are fetched per chunk
+                // the next tile's tables were requested ahead of its first stage, whose ring loads every wave
+                // waited for before the barrier of this tile's last stage
+                const unsigned next_tab = tab_base + (tb ^ 1) * T::kBytes;
+                if (C::kWgsPerCu == 1) {   // starts the next tile's accumulators on the way
+                    stream_epilogue<C>(p, cur.m0, cur.o0, acc, lds_base + C::kOffStaging + wave * C::kWaveStage, tab, more ? next_tab : 0u,
+                                       nxt.p.off, lane, wave);
+                } else {   // half the registers and a second wave on the SIMD to cover LDS round trips: constants are fetched per chunk
                     epilogue<C, false>(p, cur.m0, cur.o0, acc, lds_base + C::kOffStaging + wave * C::kWaveStage, tab, lane, wave, 0);
+                    if (more) init_acc<C>(acc, next_tab, nxt.p.off, lane, wave, 0);
+                }
                 s = 0;
                 if (more) {
-                    // the next tile's tables were requested ahead of its first stage, whose ring loads every wave
-                    // waited for before the barrier of this tile's last stage
-                    init_acc<C>(acc, tab_base + (tb ^ 1) * T::kBytes, nxt.p.off, lane, wave, 0);
                     cur = nxt;
                     tb ^= 1;
                     more = sched.next(nxt, wave, lane);
