@@ -152,6 +152,10 @@ def decode_step(device, n_iter=30, rowmajor_too=False):
         qgroup.run()
         group.run()
     smed, _ = time_launches(whole_step, 3, n_iter)
+    graph = torch.cuda.CUDAGraph()                 # the same two launches as one HIP graph
+    with torch.cuda.graph(graph):
+        whole_step()
+    gmed, _ = time_launches(graph.replay, 3, n_iter)
     q_bytes = float(sum(5.0 * s.M * s.K for s in specs))
     return {"workload": "config 4: RAR-XXL-shaped decode step, 72 linears, M = 128, one grouped launch",
             "us": med * 1e6, "gbs": all_bytes / med / 1e9, "weight_gbs": w_bytes / med / 1e9,
@@ -162,7 +166,7 @@ def decode_step(device, n_iter=30, rowmajor_too=False):
                          "kernel": "stwq::linear_stream_kernel", "avg_launch_us": mean * 1e6},
             "rowmajor_weights_us": None if rmed is None else rmed * 1e6,
             "quantize_72_launches_us": qmed * 1e6, "quantize_grouped_us": qgmed * 1e6,
-            "step_us": smed * 1e6, "step_gbs": (all_bytes + q_bytes) / smed / 1e9,
+            "step_us": smed * 1e6, "step_graph_replay_us": gmed * 1e6, "step_gbs": (all_bytes + q_bytes) / smed / 1e9,
             "step_frac_hbm_peak": (all_bytes + q_bytes) / smed / 1e9 / HBM_PEAK_GBS}
 
 

@@ -18,6 +18,9 @@
  *    8-bit code is STORED in int8 as code - 128 and used with zero point z - 128 (code - z is
  *    unchanged); 6-bit codes 0..63 are stored as they are.  Weight codes are symmetric,
  *    -(2^(b-1) - 1) .. 2^(b-1) - 1.
+ *  - The launching entry points allocate nothing, clear nothing with memset and never synchronise with the
+ *    host: after one ordinary call (which sets kernel attributes and caches the device's unit count) they can
+ *    be recorded into a HIP graph on a capturing stream and replayed.
  *  - fp32 arithmetic that decides an integer is fixed (each step rounds once, no fused
  *    multiply-add): v = (x * inv_s[c]) * inv_delta[t]; r = round-half-even(v);
  *    code = clamp(r + float(z_t), 0, 2^b - 1).

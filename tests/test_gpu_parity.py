@@ -373,3 +373,55 @@ def test_wide_and_narrow_tiles_in_one_launch():
     for sch in ("wide", "narrow"):
         y2 = layer.linear(q, schedule=SCHEDULES[sch])
         assert torch.equal(y2, y), sch
+
+
+def test_graph_replay_of_a_decode_step():
+    """The grouped quantization and the packed grouped linear of a small decode step captured into one HIP graph
+    (no allocation, no memset, no host synchronisation inside the library's launch path) and replayed several times
+    with eager work in between: every replay gives the eager launch's bits, also after the input has changed."""
+    specs = wl.config_linears(4, blocks=2)
+    qproblems, problems, xs = [], [], []
+    for spec in specs:
+        w, b, xc, xt = G.make_case(spec)
+        t0 = wl.decode_position(spec)
+        pack = G.oracle_pack(spec, xc, w, b)
+        layer = G.gpu_layer(spec, xc, w, b, pack["s"])
+        packed = torch.empty(P.stwq_packed_weight_bytes(spec.N, spec.K), dtype=torch.int8, device=G.DEV)
+        P.stwq_pack_weights(layer.wq, packed)
+        x = G.dev(xt)
+        q = torch.zeros((spec.M, spec.K), dtype=torch.int8, device=G.DEV)
+        qproblems.append(dict(x=x, L=1, inv_s=layer.inv_s, inv_delta=layer.inv_delta[t0:t0 + 1], zp=layer.zp[t0:t0 + 1],
+                              a_bits=spec.a_bits, q=q))
+        problems.append(dict(q=q, wq=packed, N=spec.N, w_layout=P.LAYOUT_PANEL32, dw=layer.dw, wsum=layer.wsum,
+                             delta=layer.delta[t0:t0 + 1], zp=layer.zp[t0:t0 + 1], a_bits=spec.a_bits, bias=layer.bias, L=1,
+                             y=torch.zeros((spec.M, spec.N), dtype=torch.bfloat16, device=G.DEV), keep=layer))
+        xs.append((x, xt, pack, t0))
+    qgroup, group = P.QuantizeGroup(qproblems), P.LinearGroup(problems)
+
+    def eager():
+        qgroup.run()
+        group.run()
+        torch.cuda.synchronize()
+        return [pr["y"].clone() for pr in problems]
+
+    want = eager()                                   # also the library's one-time set-up, outside the capture
+    for (x, xt, pack, t0), y in zip(xs, want):
+        _, _, y_ref = O.forward(pack, xt, t0=t0)
+        G.check_bf16(y, y_ref, "eager decode step", pack["bias"])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        qgroup.run()
+        group.run()
+    for rep in range(4):
+        if rep == 2:                                 # another input in the same buffers
+            for x, _, _, _ in xs:
+                x.mul_(-0.75)
+            want = eager()
+        for pr in problems:
+            pr["y"].zero_()
+            pr["q"].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (pr, y) in enumerate(zip(problems, want)):
+            assert torch.equal(pr["y"], y), f"replay {rep}, linear {i}"
